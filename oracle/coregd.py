@@ -1,0 +1,54 @@
+"""CORE-GD (Algorithm 2 of the paper) on a ridge-regression objective, fp64, CPU.
+
+TEST INFRASTRUCTURE ONLY (see ``core_oracle.c``).
+
+Objective (Eq. (problem), Section 1: f is the average of the machines' f_i):
+    f(x)   = 1/2 ||A x - b||^2 + lam/2 ||x||^2
+    f_c(x) = n/2 ||A_c x - b_c||^2 + lam/2 ||x||^2,   c = 1..n,  rows split over clients
+so that f = (1/n) sum_c f_c and grad f_c = n A_c^T (A_c x - b_c) + lam x.
+
+Each round follows Algorithm 2: fresh xi_1..xi_m from the common generator
+(counter ``round = k``), machine c forms p_cj = <grad f_c(x^k), xi_j>, the
+projections are combined over c (as the mean, Eq. (tildefdef)), every machine
+reconstructs the estimator and steps x^{k+1} = x^k - h * estimator.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import core_round
+
+
+def ridge_loss(A, b, lam, x):
+    r = A @ x - b
+    return 0.5 * float(r @ r) + 0.5 * lam * float(x @ x)
+
+
+def ridge_solution(A, b, lam):
+    """Closed form x* = (A^T A + lam I)^-1 A^T b."""
+    d = A.shape[1]
+    return np.linalg.solve(A.T @ A + lam * np.eye(d), A.T @ b)
+
+
+def client_gradients(A, b, lam, x, n):
+    """Rows of A split into n contiguous equal blocks; returns G [n, d] with G[c] = grad f_c(x)."""
+    rows = A.shape[0] // n
+    G = np.empty((n, A.shape[1]), dtype=np.float64)
+    for c in range(n):
+        Ac = A[c * rows:(c + 1) * rows]
+        bc = b[c * rows:(c + 1) * rows]
+        G[c] = n * (Ac.T @ (Ac @ x - bc)) + lam * x
+    return G
+
+
+def core_gd(A, b, lam, n, m, h, rounds, seed, x0=None, first_round=0):
+    """Run Algorithm 2 for ``rounds`` rounds; returns (x, losses[rounds+1])."""
+    d = A.shape[1]
+    x = np.zeros(d) if x0 is None else np.array(x0, dtype=np.float64)
+    losses = [ridge_loss(A, b, lam, x)]
+    for k in range(rounds):
+        G = client_gradients(A, b, lam, x, n)
+        _, _, gtilde = core_round(seed, first_round + k, G, m)
+        x = x - h * gtilde
+        losses.append(ridge_loss(A, b, lam, x))
+    return x, np.array(losses)

@@ -1,0 +1,91 @@
+"""Pins that run the oracle's round inside CORE-GD (Algorithm 2) on a tiny ridge problem.
+
+Closed form x* = (A^T A + lam I)^-1 A^T b; the exact expected one-step change on a
+quadratic (second-order expansion in the proof of Theorem 4.2, which is an equality
+when f is quadratic, with the moments of Lemma 3.1 / proof of Lemma 3.2); and the
+contraction factor of Theorem 4.2 in the regime it assumes (m <= tr(A)/L,
+h = m / (4 tr(A))).
+"""
+import numpy as np
+
+from oracle import coregd
+
+
+def _problem(d=16, rows=32, n=4, lam=1e-2, seed=0, decay=1.0):
+    rng = np.random.default_rng(seed)
+    U, _ = np.linalg.qr(rng.standard_normal((rows, d)))
+    V, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    s = np.arange(1, d + 1, dtype=np.float64) ** (-decay)
+    A = (U * s) @ V.T
+    x_true = rng.standard_normal(d)
+    b = A @ x_true + 0.01 * rng.standard_normal(rows)
+    return A, b, lam, n
+
+
+def test_client_gradients_average_to_the_full_gradient():
+    A, b, lam, n = _problem()
+    x = np.random.default_rng(1).standard_normal(A.shape[1])
+    G = coregd.client_gradients(A, b, lam, x, n)
+    full = A.T @ (A @ x - b) + lam * x
+    np.testing.assert_allclose(G.mean(axis=0), full, rtol=1e-12, atol=1e-12)
+    xs = coregd.ridge_solution(A, b, lam)
+    assert np.linalg.norm(A.T @ (A @ xs - b) + lam * xs) < 1e-12
+
+
+def test_exact_one_step_expectation_on_a_quadratic():
+    A, b, lam, n = _problem()
+    d = A.shape[1]
+    H = A.T @ A + lam * np.eye(d)
+    x = np.random.default_rng(2).standard_normal(d)
+    g = A.T @ (A @ x - b) + lam * x
+    f0 = coregd.ridge_loss(A, b, lam, x)
+    m, h, S = 4, 0.3, 20000
+    expected = f0 - h * (g @ g) + 0.5 * h * h * ((1 + 1.0 / m) * (g @ H @ g)
+                                                 + np.trace(H) * (g @ g) / m)
+    vals = np.empty(S)
+    for s in range(S):
+        _, losses = coregd.core_gd(A, b, lam, n, m, h, 1, seed=100 + s, x0=x)
+        vals[s] = losses[1]
+    assert abs(vals.mean() - expected) < 4.5 * vals.std() / np.sqrt(S)
+
+
+def test_theorem_contraction_in_its_regime():
+    # flat-ish spectrum so that tr(H)/L is comfortably above m
+    A, b, lam, n = _problem(decay=0.25)
+    d = A.shape[1]
+    H = A.T @ A + lam * np.eye(d)
+    ev = np.linalg.eigvalsh(H)
+    L, mu, trH = ev[-1], ev[0], ev.sum()
+    m = 2
+    assert m <= trH / L
+    h = m / (4.0 * trH)
+    rate = 1.0 - 3.0 * m * mu / (16.0 * trH)
+    xs = coregd.ridge_solution(A, b, lam)
+    fstar = coregd.ridge_loss(A, b, lam, xs)
+    x0 = np.zeros(d)
+    gap0 = coregd.ridge_loss(A, b, lam, x0) - fstar
+    S, K = 400, 25
+    gaps = np.empty((S, K + 1))
+    for s in range(S):
+        _, losses = coregd.core_gd(A, b, lam, n, m, h, K, seed=7000 + s, x0=x0)
+        gaps[s] = losses - fstar
+    mean_gap = gaps.mean(axis=0)
+    sem = gaps.std(axis=0) / np.sqrt(S)
+    for k in range(1, K + 1):
+        assert mean_gap[k] <= rate ** k * gap0 + 4.5 * sem[k]
+    assert mean_gap[K] < mean_gap[0]
+
+
+def test_core_gd_reaches_the_closed_form_solution():
+    A, b, lam, n = _problem(d=8, rows=16, lam=0.1)
+    d = A.shape[1]
+    H = A.T @ A + lam * np.eye(d)
+    ev = np.linalg.eigvalsh(H)
+    m = 8
+    # the step the proof optimises before it specialises m <= tr(A)/L
+    h = m / (3.0 * ev.sum() + 2.0 * m * ev[-1])
+    xs = coregd.ridge_solution(A, b, lam)
+    fstar = coregd.ridge_loss(A, b, lam, xs)
+    x, losses = coregd.core_gd(A, b, lam, n, m, h, 600, seed=5)
+    assert losses[-1] - fstar < 1e-6 * (losses[0] - fstar)
+    assert np.linalg.norm(x - xs) < 1e-2 * np.linalg.norm(xs)
