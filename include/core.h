@@ -1,0 +1,130 @@
+/*
+ * core.h -- C ABI of the CORE (Common Random Reconstruction) hot path for AMD MI355X (gfx950).
+ *
+ * The method is that of "CORE: Common Random Reconstruction for Distributed
+ * Optimization with Provable Low Communication Complexity" (arXiv 2309.13307):
+ *
+ *   compression     p_j = <a, xi_j>,  j = 1..m              (Algorithm 1, Section 3)
+ *   reconstruction  a~  = (1/m) sum_j p_j xi_j              (Eq. (reconstruction), Section 3)
+ *   n machines      g~  = (1/(n m)) sum_i sum_j <g_i, xi_j> xi_j
+ *                                                           (Eq. (tildefdef), Section 4;
+ *                                                            Algorithm 2, the three
+ *                                                            communication lines)
+ *
+ * xi_1..xi_m ~ N(0, I_d) come from a generator every machine shares (Algorithm 1,
+ * REQUIRE line).  They are never stored: each kernel regenerates the values it
+ * needs in registers from (seed, round, j, i):
+ *
+ *   Philox4x32-10 with key (seed lo32, seed hi32) and counter
+ *   (q = floor(i/4), j, round lo32, round hi32) yields four words x0..x3;
+ *   u1 = ((xa>>8)+1) 2^-24, u2 = (xb>>8) 2^-24, r = sqrt(-2 ln u1),
+ *   (x0,x1) -> xi_j[4q] = r cos(2 pi u2), xi_j[4q+1] = r sin(2 pi u2); (x2,x3) -> xi_j[4q+2], xi_j[4q+3].
+ *   j and i are 0-based.  A new `round` gives fresh vectors (Algorithm 1 / Algorithm 2,
+ *   "generate fresh i.i.d. Gaussian vectors"); all n clients of a call share them.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     allocates nothing, frees nothing and keeps no pointer after it returns.
+ *   - Work is enqueued on `stream` (a hipStream_t; NULL = the default stream) and
+ *     the call returns without synchronising.  Outputs are overwritten, never
+ *     accumulated into.  Results are a pure function of the arguments and
+ *     bit-identical from run to run on the same device and build (all sums run
+ *     in a fixed order; no floating-point atomics).
+ *   - Return value: CORE_OK (0) or a negative CORE_ERR_* code.  Arguments are
+ *     validated on the host before anything is launched, so a failing call
+ *     enqueues nothing and writes nothing.
+ *   - Limits: 1 <= d <= 2^34, 1 <= m <= 2^32-1, 1 <= n <= 65535, ld >= d.
+ *     fp32 pointers must be 4-byte aligned, bf16 pointers 2-byte aligned; rows of G
+ *     may start at any element.  gtilde is written with 128-bit stores when it is
+ *     16-byte aligned and with scalar stores otherwise.
+ *   - Arithmetic: fp32 throughout on the device; per-(client, vector) sums are
+ *     blocked (256-coordinate inner sums, then per-chunk sums, then an fp64 sum
+ *     over chunks) so that rounding error stays near fp32 epsilon at any d.
+ */
+#ifndef CORE_H_
+#define CORE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CORE_DTYPE_F32 = 0,  /* IEEE binary32 */
+    CORE_DTYPE_BF16 = 1  /* upper 16 bits of a binary32, widened exactly on load */
+} core_dtype;
+
+typedef void *core_stream; /* hipStream_t */
+
+enum {
+    CORE_OK = 0,
+    CORE_ERR_INVALID_ARGUMENT = -1,   /* NULL required pointer, zero or out-of-range size, ld < d, unknown dtype */
+    CORE_ERR_MISALIGNED = -2,         /* pointer not aligned to its element size */
+    CORE_ERR_WORKSPACE_TOO_SMALL = -3,/* ws_bytes < core_workspace_bytes(d, m, n) */
+    CORE_ERR_HIP = -4,                /* the HIP runtime refused a launch (see core_last_hip_error) */
+    CORE_ERR_NO_DEVICE = -5           /* no usable GPU in this process */
+};
+
+/* Static, human-readable text for a return code. */
+const char *core_strerror(int code);
+
+/* hipError_t of the most recent CORE_ERR_HIP on the calling thread (0 if none). */
+int core_last_hip_error(void);
+
+/* Bytes of device scratch the compress/round entry points need for these sizes
+ * (per-chunk partial projections and the staged cross-chunk sums).  Returns 0 if
+ * the sizes are out of range.  The scratch needs 16-byte alignment and carries
+ * no state between calls. */
+size_t core_workspace_bytes(uint64_t d, uint32_t m, uint32_t n);
+
+/* Algorithm 1, compression line, for one vector:  p[j] = <g, xi_j>, j < m.
+ *   g  [d] device, dtype dt;  p [m] device fp32 (out);  ws device scratch. */
+int core_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m,
+                  const void *g, core_dtype dt,
+                  float *p,
+                  void *ws, size_t ws_bytes, core_stream stream);
+
+/* Algorithm 2, "machine i sends p_ij" for n machines batched on one device, and the
+ * combination of Eq. (tildefdef):
+ *   P[c][j]  = <G[c], xi_j>                     c < n, j < m
+ *   pbar[j]  = (1/n) sum_c P[c][j]
+ *   G    [n][ld] device, row-major, dtype dt, ld >= d (elements)
+ *   P    [n][m]  device fp32 (out), may be NULL when only the mean is wanted
+ *   pbar [m]     device fp32 (out) */
+int core_compress_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                          const void *G, core_dtype dt, uint64_t ld,
+                          float *P, float *pbar,
+                          void *ws, size_t ws_bytes, core_stream stream);
+
+/* Eq. (reconstruction):  gtilde[i] = scale * sum_{j<m} pbar[j] * xi_j[i],  i < d.
+ * scale = 1/m is the paper's estimator of the mean gradient; scale = n/m applied to
+ * the client mean gives the sum-over-machines form written in Algorithm 2.
+ *   pbar [m] device fp32;  gtilde [d] device fp32 (out). */
+int core_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m,
+                     const float *pbar, float scale,
+                     float *gtilde, core_stream stream);
+
+/* One communication round of Algorithm 2 without the x update:
+ * core_compress_batched(P = NULL) followed by core_reconstruct(scale = 1/m),
+ * i.e. Eq. (tildefdef).  pbar [m] and gtilde [d] are both outputs. */
+int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+               const void *G, core_dtype dt, uint64_t ld,
+               float *pbar, float *gtilde,
+               void *ws, size_t ws_bytes, core_stream stream);
+
+/* ---- test-only exports: raw generator output -------------------------------- */
+
+/* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks.  out device uint32. */
+int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,
+                      uint32_t *out, core_stream stream);
+
+/* out[t] = xi_j[i0 + t] as the kernels compute it (fp32), t < count.  out device fp32. */
+int core_debug_xi(uint64_t seed, uint64_t round, uint32_t j, uint64_t i0, uint64_t count,
+                  float *out, core_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CORE_H_ */

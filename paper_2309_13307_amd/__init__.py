@@ -1,0 +1,9 @@
+"""MI355X-native hot path of CORE (Common Random Reconstruction, arXiv 2309.13307).
+
+The product is the C-ABI library ``libcore_hip.so`` (see ``include/core.h``); this package is its
+thin Python binding plus the seeded synthetic-input generators used by tests and the benchmark.
+"""
+from .binding import (  # noqa: F401
+    CoreError, alloc_workspace, core_compress, core_compress_batched, core_debug_philox,
+    core_debug_xi, core_reconstruct, core_round, core_workspace_bytes, load_library, strerror,
+)

@@ -1,0 +1,200 @@
+"""ctypes binding of the C ABI in ``include/core.h``.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libcore_hip.so``.  torch is used for device memory and the stream handle.  There is no
+CPU fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+DTYPE_F32 = 0
+DTYPE_BF16 = 1
+
+OK = 0
+ERR_INVALID_ARGUMENT = -1
+ERR_MISALIGNED = -2
+ERR_WORKSPACE_TOO_SMALL = -3
+ERR_HIP = -4
+ERR_NO_DEVICE = -5
+
+EXPORTS = (
+    "core_strerror", "core_last_hip_error", "core_workspace_bytes", "core_compress",
+    "core_compress_batched", "core_reconstruct", "core_round", "core_debug_philox", "core_debug_xi",
+)
+
+
+class CoreError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libcore_hip.so, building it only if no built library is present."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library()
+    L = ctypes.CDLL(_build.LIB_PATH)
+    u64, u32, i32, vp, sz, f32 = (ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p,
+                                  ctypes.c_size_t, ctypes.c_float)
+    L.core_strerror.argtypes = [i32]
+    L.core_strerror.restype = ctypes.c_char_p
+    L.core_last_hip_error.argtypes = []
+    L.core_last_hip_error.restype = i32
+    L.core_workspace_bytes.argtypes = [u64, u32, u32]
+    L.core_workspace_bytes.restype = sz
+    L.core_compress.argtypes = [u64, u64, u64, u32, vp, i32, vp, vp, sz, vp]
+    L.core_compress.restype = i32
+    L.core_compress_batched.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz, vp]
+    L.core_compress_batched.restype = i32
+    L.core_reconstruct.argtypes = [u64, u64, u64, u32, vp, f32, vp, vp]
+    L.core_reconstruct.restype = i32
+    L.core_round.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz, vp]
+    L.core_round.restype = i32
+    L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
+    L.core_debug_philox.restype = i32
+    L.core_debug_xi.argtypes = [u64, u64, u32, u64, u64, vp, vp]
+    L.core_debug_xi.restype = i32
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return load_library().core_strerror(code).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != OK:
+        raise CoreError(code, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError(f"G must be float32 or bfloat16, got {t.dtype}")
+
+
+def _require_cuda(*tensors) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("all tensors must live on the GPU")
+
+
+def core_workspace_bytes(d: int, m: int, n: int) -> int:
+    return int(load_library().core_workspace_bytes(d, m, n))
+
+
+def alloc_workspace(d: int, m: int, n: int, device="cuda") -> torch.Tensor:
+    nbytes = core_workspace_bytes(d, m, n)
+    if nbytes == 0:
+        raise CoreError(ERR_INVALID_ARGUMENT, "core_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def core_compress(seed: int, rnd: int, g: torch.Tensor, m: int, p: torch.Tensor | None = None,
+                  ws: torch.Tensor | None = None) -> torch.Tensor:
+    """p[j] = <g, xi_j>.  g: [d] fp32/bf16 on the GPU."""
+    _require_cuda(g, p, ws)
+    if g.dim() != 1 or not g.is_contiguous():
+        raise ValueError("g must be a contiguous 1-D tensor")
+    d = g.numel()
+    if p is None:
+        p = torch.empty(m, dtype=torch.float32, device=g.device)
+    if ws is None:
+        ws = alloc_workspace(d, m, 1, g.device)
+    rc = load_library().core_compress(seed, rnd, d, m, g.data_ptr(), _dtype_code(g), p.data_ptr(),
+                                      ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "core_compress")
+    return p
+
+
+def core_compress_batched(seed: int, rnd: int, G: torch.Tensor, m: int, d: int | None = None,
+                          P: torch.Tensor | None = None, pbar: torch.Tensor | None = None,
+                          ws: torch.Tensor | None = None, want_P: bool = True):
+    """P[c, j] = <G[c, :d], xi_j>, pbar = mean over clients.  G: [n, ld] with unit inner stride."""
+    _require_cuda(G, P, pbar, ws)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    if P is None and want_P:
+        P = torch.empty((n, m), dtype=torch.float32, device=G.device)
+    if pbar is None:
+        pbar = torch.empty(m, dtype=torch.float32, device=G.device)
+    if ws is None:
+        ws = alloc_workspace(d, m, n, G.device)
+    rc = load_library().core_compress_batched(seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld,
+                                              P.data_ptr() if P is not None else None,
+                                              pbar.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "core_compress_batched")
+    return P, pbar
+
+
+def core_reconstruct(seed: int, rnd: int, d: int, pbar: torch.Tensor, scale: float,
+                     gtilde: torch.Tensor | None = None) -> torch.Tensor:
+    """gtilde[i] = scale * sum_j pbar[j] xi_j[i]."""
+    _require_cuda(pbar, gtilde)
+    if pbar.dtype != torch.float32 or pbar.dim() != 1 or not pbar.is_contiguous():
+        raise ValueError("pbar must be a contiguous 1-D float32 tensor")
+    m = pbar.numel()
+    if gtilde is None:
+        gtilde = torch.empty(d, dtype=torch.float32, device=pbar.device)
+    rc = load_library().core_reconstruct(seed, rnd, d, m, pbar.data_ptr(), scale, gtilde.data_ptr(),
+                                         _stream())
+    _check(rc, "core_reconstruct")
+    return gtilde
+
+
+def core_round(seed: int, rnd: int, G: torch.Tensor, m: int, d: int | None = None,
+               pbar: torch.Tensor | None = None, gtilde: torch.Tensor | None = None,
+               ws: torch.Tensor | None = None):
+    """One CORE round on n batched clients: returns (pbar [m], gtilde [d])."""
+    _require_cuda(G, pbar, gtilde, ws)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    if pbar is None:
+        pbar = torch.empty(m, dtype=torch.float32, device=G.device)
+    if gtilde is None:
+        gtilde = torch.empty(d, dtype=torch.float32, device=G.device)
+    if ws is None:
+        ws = alloc_workspace(d, m, n, G.device)
+    rc = load_library().core_round(seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld,
+                                   pbar.data_ptr(), gtilde.data_ptr(), ws.data_ptr(), ws.numel(),
+                                   _stream())
+    _check(rc, "core_round")
+    return pbar, gtilde
+
+
+def core_debug_philox(seed: int, rnd: int, j: int, q0: int, nblocks: int, device="cuda") -> torch.Tensor:
+    out = torch.empty((nblocks, 4), dtype=torch.int32, device=device)
+    rc = load_library().core_debug_philox(seed, rnd, j, q0, nblocks, out.data_ptr(), _stream())
+    _check(rc, "core_debug_philox")
+    return out
+
+
+def core_debug_xi(seed: int, rnd: int, j: int, i0: int, count: int, device="cuda") -> torch.Tensor:
+    out = torch.empty(count, dtype=torch.float32, device=device)
+    rc = load_library().core_debug_xi(seed, rnd, j, i0, count, out.data_ptr(), _stream())
+    _check(rc, "core_debug_xi")
+    return out

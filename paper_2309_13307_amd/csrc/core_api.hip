@@ -1,0 +1,255 @@
+// Host side of the C ABI declared in include/core.h: argument validation, launch planning
+// and kernel launches.  Nothing here touches device memory from the host or synchronises.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/core.h"
+#include "core_kernels.hpp"
+
+namespace {
+
+using namespace core;
+
+thread_local int g_last_hip_error = 0;
+
+constexpr uint64_t kMaxD = 1ull << 34;
+constexpr uint32_t kMaxN = 65535u;
+constexpr uint32_t kMaxClientsPerPass = 16;   // accumulators held in registers per lane
+constexpr uint32_t kTargetBlocks = 8192;      // projection blocks wanted: 4 per resident slot
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Plan {
+    uint32_t jtiles;
+    uint32_t nchunks;
+    uint32_t tiles_per_chunk;
+    uint32_t S;            // slices of the cross-chunk sum
+    size_t part_off, part2_off, total;
+};
+
+// Split d into chunks of whole 256-coordinate tiles so that (chunks x vector tiles) fills the
+// chip several times over; sizes depend only on (d, m, n).
+bool make_plan(uint64_t d, uint32_t m, uint32_t n, Plan& p)
+{
+    if (d == 0 || d > kMaxD || m == 0 || n == 0 || n > kMaxN) return false;
+    const uint64_t tiles_total = ceil_div(d, kTile);
+    p.jtiles = (uint32_t)ceil_div(m, kThreads);
+    uint64_t want = ceil_div(kTargetBlocks, p.jtiles);
+    if (want < 1) want = 1;
+    if (want > tiles_total) want = tiles_total;
+    p.tiles_per_chunk = (uint32_t)ceil_div(tiles_total, want);
+    p.nchunks = (uint32_t)ceil_div(tiles_total, p.tiles_per_chunk);
+    uint32_t S = p.nchunks / 64u;
+    if (S < 1) S = 1;
+    if (S > 16) S = 16;
+    p.S = S;
+    const uint64_t E = (uint64_t)n * m;
+    size_t off = 0;
+    p.part_off = off;   off = align_up(off + (size_t)p.nchunks * E * sizeof(float), 256);
+    p.part2_off = off;  off = align_up(off + (size_t)S * E * sizeof(double), 256);
+    p.total = off;
+    return true;
+}
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return CORE_ERR_HIP;
+}
+
+int check_device()
+{
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
+        (void)hipGetLastError();
+        return CORE_ERR_NO_DEVICE;
+    }
+    return CORE_OK;
+}
+
+bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+template <int NC>
+hipError_t launch_project(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+{
+    if (bf16) hipLaunchKernelGGL((project_kernel<NC, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+    else      hipLaunchKernelGGL((project_kernel<NC, false>), dim3(blocks), dim3(kThreads), 0, st, a);
+    return hipGetLastError();
+}
+
+int validate_compress(uint64_t d, uint32_t m, uint32_t n, const void* G, core_dtype dt, uint64_t ld,
+                      const float* P, const float* pbar, const void* ws, size_t ws_bytes, Plan& plan)
+{
+    if (!G || !pbar || !ws) return CORE_ERR_INVALID_ARGUMENT;
+    if (dt != CORE_DTYPE_F32 && dt != CORE_DTYPE_BF16) return CORE_ERR_INVALID_ARGUMENT;
+    if (ld < d) return CORE_ERR_INVALID_ARGUMENT;
+    if (!make_plan(d, m, n, plan)) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(G, dt == CORE_DTYPE_F32 ? 4 : 2)) return CORE_ERR_MISALIGNED;
+    if (!aligned_to(pbar, 4) || (P && !aligned_to(P, 4)) || !aligned_to(ws, 16)) return CORE_ERR_MISALIGNED;
+    if (ws_bytes < plan.total) return CORE_ERR_WORKSPACE_TOO_SMALL;
+    return CORE_OK;
+}
+
+int validate_reconstruct(uint64_t d, uint32_t m, const float* pbar, const float* gtilde)
+{
+    if (!pbar || !gtilde) return CORE_ERR_INVALID_ARGUMENT;
+    if (d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(pbar, 4) || !aligned_to(gtilde, 4)) return CORE_ERR_MISALIGNED;
+    return CORE_OK;
+}
+
+int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                     const void* G, core_dtype dt, uint64_t ld, float* P, float* pbar,
+                     void* ws, const Plan& plan, hipStream_t st)
+{
+    char* base = (char*)ws;
+    float* part = (float*)(base + plan.part_off);
+    double* part2 = (double*)(base + plan.part2_off);
+
+    ProjectArgs a;
+    a.G = G; a.ld = ld; a.d = d; a.m = m; a.n = n;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
+    a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
+    a.jtiles = plan.jtiles; a.nchunks = plan.nchunks; a.tiles_per_chunk = plan.tiles_per_chunk;
+    a.part = part;
+    const uint32_t blocks = (uint32_t)(ceil_div(plan.nchunks, 8) * 8 * plan.jtiles);
+    const bool bf16 = (dt == CORE_DTYPE_BF16);
+
+    for (uint32_t c0 = 0; c0 < n; c0 += kMaxClientsPerPass) {
+        const uint32_t nc = (n - c0 < kMaxClientsPerPass) ? (n - c0) : kMaxClientsPerPass;
+        a.c0 = c0; a.nc = nc;
+        hipError_t e;
+        if (nc <= 1)      e = launch_project<1>(a, bf16, blocks, st);
+        else if (nc <= 2) e = launch_project<2>(a, bf16, blocks, st);
+        else if (nc <= 4) e = launch_project<4>(a, bf16, blocks, st);
+        else if (nc <= 8) e = launch_project<8>(a, bf16, blocks, st);
+        else              e = launch_project<16>(a, bf16, blocks, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+
+    const uint64_t E = (uint64_t)n * m;
+    hipLaunchKernelGGL(reduce_chunks_kernel, dim3((uint32_t)ceil_div(E, 64), plan.S), dim3(kThreads), 0, st,
+                       part, E, plan.nchunks, plan.S, part2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    hipLaunchKernelGGL(reduce_clients_kernel, dim3((uint32_t)ceil_div(m, kThreads)), dim3(kThreads), 0, st,
+                       part2, m, n, plan.S, P, pbar);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return CORE_OK;
+}
+
+int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
+                        float scale, float* gtilde, hipStream_t st)
+{
+    ReconArgs a;
+    a.pbar = pbar; a.gtilde = gtilde; a.d = d; a.m = m; a.scale = scale;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
+    a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
+    a.vec_store = aligned_to(gtilde, 16) ? 1 : 0;
+    const uint64_t nblk = ceil_div(d, 4);
+    const uint32_t blocks = (uint32_t)ceil_div(nblk, (uint64_t)kThreads * kReconBlocks);
+    hipLaunchKernelGGL(reconstruct_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return CORE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* core_strerror(int code)
+{
+    switch (code) {
+        case CORE_OK: return "success";
+        case CORE_ERR_INVALID_ARGUMENT: return "invalid argument (null pointer, zero or out-of-range size, ld < d, or unknown dtype)";
+        case CORE_ERR_MISALIGNED: return "pointer not aligned to its element size (workspace: 16 bytes)";
+        case CORE_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than core_workspace_bytes(d, m, n)";
+        case CORE_ERR_HIP: return "HIP runtime error on launch (see core_last_hip_error)";
+        case CORE_ERR_NO_DEVICE: return "no usable GPU device";
+        default: return "unknown error code";
+    }
+}
+
+int core_last_hip_error(void) { return g_last_hip_error; }
+
+size_t core_workspace_bytes(uint64_t d, uint32_t m, uint32_t n)
+{
+    Plan p;
+    if (!make_plan(d, m, n, p)) return 0;
+    return p.total;
+}
+
+int core_compress_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                          const void* G, core_dtype dt, uint64_t ld, float* P, float* pbar,
+                          void* ws, size_t ws_bytes, core_stream stream)
+{
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, P, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    return enqueue_compress(seed, round, d, m, n, G, dt, ld, P, pbar, ws, plan, (hipStream_t)stream);
+}
+
+int core_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const void* g, core_dtype dt,
+                  float* p, void* ws, size_t ws_bytes, core_stream stream)
+{
+    // one client: the mean over clients is the projection itself
+    return core_compress_batched(seed, round, d, m, 1, g, dt, d, nullptr, p, ws, ws_bytes, stream);
+}
+
+int core_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
+                     float scale, float* gtilde, core_stream stream)
+{
+    int rc = validate_reconstruct(d, m, pbar, gtilde);
+    if (rc != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    return enqueue_reconstruct(seed, round, d, m, pbar, scale, gtilde, (hipStream_t)stream);
+}
+
+int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n, const void* G,
+               core_dtype dt, uint64_t ld, float* pbar, float* gtilde, void* ws, size_t ws_bytes,
+               core_stream stream)
+{
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = validate_reconstruct(d, m, pbar, gtilde)) != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
+    if (rc != CORE_OK) return rc;
+    return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream);
+}
+
+int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,
+                      uint32_t* out, core_stream stream)
+{
+    if (!out || nblocks == 0 || nblocks > (1ull << 32) || q0 + nblocks > (1ull << 32))
+        return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(out, 4)) return CORE_ERR_MISALIGNED;
+    int rc = check_device();
+    if (rc != CORE_OK) return rc;
+    hipLaunchKernelGGL(debug_philox_kernel, dim3((uint32_t)ceil_div(nblocks, kThreads)), dim3(kThreads), 0,
+                       (hipStream_t)stream, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)round,
+                       (uint32_t)(round >> 32), j, q0, nblocks, out);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
+}
+
+int core_debug_xi(uint64_t seed, uint64_t round, uint32_t j, uint64_t i0, uint64_t count, float* out,
+                  core_stream stream)
+{
+    if (!out || count == 0 || count > (1ull << 32) || i0 + count > kMaxD) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(out, 4)) return CORE_ERR_MISALIGNED;
+    int rc = check_device();
+    if (rc != CORE_OK) return rc;
+    hipLaunchKernelGGL(debug_xi_kernel, dim3((uint32_t)ceil_div(count, kThreads)), dim3(kThreads), 0,
+                       (hipStream_t)stream, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)round,
+                       (uint32_t)(round >> 32), j, i0, count, out);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,273 @@
+// HIP kernels of the CORE hot path for gfx950 (wave64, 256 CUs in 8 XCDs, 160 KB LDS per CU).
+//
+//   project_kernel      Algorithm 1 compression line / Algorithm 2 "machine i sends p_ij":
+//                       per-chunk partial sums of P[c][j] = <G[c], xi_j>
+//   reduce_*_kernel     sum of the partials over chunks (fp64, fixed order) and the client mean
+//                       pbar[j] = (1/n) sum_c P[c][j]            (Eq. (tildefdef))
+//   reconstruct_kernel  gtilde[i] = scale * sum_j pbar[j] xi_j[i]  (Eq. (reconstruction))
+//
+// Both heavy kernels are bound by VALU issue (the generator: ~40 integer/transcendental
+// lane-ops per normal), not by HBM: G is read once per 256-vector tile and gtilde written once.
+// The lane mappings are chosen to make the generator as cheap as possible:
+//   - projection: lanes run over the vector index j, all lanes of a wave share the Philox
+//     block q.  Then counter words 0, 2, 3 are wave-uniform, the scalar unit does 4 of the 20
+//     Philox products, every lane owns its (j, client) sums (no cross-lane reduction), and the
+//     wave-uniform G values arrive as LDS broadcast reads (VGPR operands; an SGPR operand
+//     would nearly double the cost of each FMA on this chip).
+//   - reconstruction: lanes run over q (coalesced 128-bit stores), j is the loop index and
+//     wave-uniform: 2 of the 20 products are scalar, pbar[j] is an LDS broadcast read.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "core_rng.hpp"
+
+namespace core {
+
+constexpr int kThreads = 256;     // threads per block in every kernel
+constexpr int kTile = 256;        // coordinates of G staged in LDS per step (64 Philox blocks)
+constexpr int kReconBlocks = 2;   // Philox blocks per thread in the reconstruction kernel
+constexpr int kPbarTile = 1024;   // pbar values staged in LDS per step
+
+struct ProjectArgs {
+    const void* G;        // [n][ld], element type by template
+    uint64_t ld;
+    uint64_t d;
+    uint32_t m;
+    uint32_t n;           // total clients (row count of the partial array)
+    uint32_t c0;          // first client of this pass
+    uint32_t nc;          // clients in this pass (<= NC)
+    uint32_t k0, k1;      // seed halves
+    uint32_t r0, r1;      // round halves
+    uint32_t jtiles;      // ceil(m / kThreads)
+    uint32_t nchunks;     // chunks of d
+    uint32_t tiles_per_chunk;
+    float* part;          // [nchunks][n][m]
+};
+
+template <bool BF16>
+__device__ __forceinline__ float load_g(const void* G, uint64_t idx)
+{
+    if constexpr (BF16) {
+        return __uint_as_float((uint32_t)((const uint16_t*)G)[idx] << 16);
+    } else {
+        return ((const float*)G)[idx];
+    }
+}
+
+template <int NC, bool BF16>
+__global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float tile[NC][kTile];
+
+    // Consecutive block ids are dealt round-robin to the 8 XCDs; keep all vector tiles
+    // of one chunk of G on one XCD so the chunk is fetched into a single L2.
+    const uint32_t b = blockIdx.x;
+    const uint32_t xcd = b & 7u;
+    const uint32_t s = b >> 3;
+    const uint32_t chunk = (s / a.jtiles) * 8u + xcd;
+    const uint32_t jt = s % a.jtiles;
+    if (chunk >= a.nchunks) return;
+
+    const uint32_t t = threadIdx.x;
+    const uint32_t j = jt * kThreads + t;
+
+    const uint64_t tiles_total = (a.d + kTile - 1) / kTile;
+    const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk;
+    uint64_t tile_end = tile_begin + a.tiles_per_chunk;
+    if (tile_end > tiles_total) tile_end = tiles_total;
+
+    float acc_outer[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc_outer[c] = 0.0f;
+
+    // register prefetch of the next tile: thread t holds coordinate i0 + t of every client
+    float pre[NC];
+    auto fetch = [&](uint64_t tl) {
+        const uint64_t i = tl * kTile + t;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            float v = 0.0f;
+            if (i < a.d && (uint32_t)c < a.nc) v = load_g<BF16>(a.G, (uint64_t)(a.c0 + c) * a.ld + i);
+            pre[c] = v;
+        }
+    };
+    if (tile_begin < tile_end) fetch(tile_begin);
+
+    for (uint64_t tl = tile_begin; tl < tile_end; ++tl) {
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < NC; ++c) tile[c][t] = pre[c];
+        __syncthreads();
+        if (tl + 1 < tile_end) fetch(tl + 1);
+
+        float acc[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
+        const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
+#pragma unroll 2
+        for (int qq = 0; qq < kTile / 4; ++qq) {
+            const Normals z = xi_block(q0 + (uint32_t)qq, j, a.r0, a.r1, a.k0, a.k1);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 g = *reinterpret_cast<const float4*>(&tile[c][4 * qq]);
+                acc[c] = fmaf(z.z0, g.x, acc[c]);
+                acc[c] = fmaf(z.z1, g.y, acc[c]);
+                acc[c] = fmaf(z.z2, g.z, acc[c]);
+                acc[c] = fmaf(z.z3, g.w, acc[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc_outer[c] += acc[c];
+    }
+
+    if (j < a.m) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if ((uint32_t)c < a.nc)
+                a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + j] = acc_outer[c];
+        }
+    }
+}
+
+// Stage A of the cross-chunk sum: part2[sy][e] = sum over this slice's chunks of part[k][e],
+// e = c*m + j.  Block = 64 outputs x 4 interleaved sub-slices; fixed order, fp64.
+__global__ void __launch_bounds__(kThreads) reduce_chunks_kernel(const float* __restrict__ part,
+                                                                 uint64_t E, uint32_t nchunks,
+                                                                 uint32_t S, double* __restrict__ part2)
+{
+    __shared__ double sh[4][64];
+    const uint32_t el = threadIdx.x & 63u;
+    const uint32_t sl = threadIdx.x >> 6;
+    const uint64_t e = (uint64_t)blockIdx.x * 64u + el;
+    const uint32_t sy = blockIdx.y;
+    double s = 0.0;
+    if (e < E) {
+        for (uint32_t k = sy * 4u + sl; k < nchunks; k += 4u * S) s += (double)part[(uint64_t)k * E + e];
+    }
+    sh[sl][el] = s;
+    __syncthreads();
+    if (sl == 0 && e < E) part2[(uint64_t)sy * E + e] = ((sh[0][el] + sh[1][el]) + sh[2][el]) + sh[3][el];
+}
+
+// Stage B: P[c][j] = sum_sy part2[sy][c*m+j];  pbar[j] = (1/n) sum_c P[c][j].
+__global__ void __launch_bounds__(kThreads) reduce_clients_kernel(const double* __restrict__ part2,
+                                                                  uint32_t m, uint32_t n, uint32_t S,
+                                                                  float* __restrict__ P,
+                                                                  float* __restrict__ pbar)
+{
+    const uint32_t j = blockIdx.x * kThreads + threadIdx.x;
+    if (j >= m) return;
+    const uint64_t E = (uint64_t)n * m;
+    double tot = 0.0;
+    for (uint32_t c = 0; c < n; ++c) {
+        double s = 0.0;
+        for (uint32_t sy = 0; sy < S; ++sy) s += part2[(uint64_t)sy * E + (uint64_t)c * m + j];
+        if (P) P[(uint64_t)c * m + j] = (float)s;
+        tot += s;
+    }
+    pbar[j] = (float)(tot / (double)n);
+}
+
+struct ReconArgs {
+    const float* pbar;    // [m]
+    float* gtilde;        // [d]
+    uint64_t d;
+    uint32_t m;
+    float scale;
+    uint32_t k0, k1, r0, r1;
+    int vec_store;        // gtilde is 16-byte aligned
+};
+
+__global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
+{
+    __shared__ float pb[kPbarTile];
+    const uint32_t t = threadIdx.x;
+    const uint64_t nblk = (a.d + 3) / 4;   // Philox blocks in the vector
+    const uint64_t qbase = (uint64_t)blockIdx.x * (kThreads * kReconBlocks) + t;
+
+    float outer[kReconBlocks][4];
+#pragma unroll
+    for (int r = 0; r < kReconBlocks; ++r)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) outer[r][k] = 0.0f;
+
+    for (uint32_t j0 = 0; j0 < a.m; j0 += kPbarTile) {
+        const uint32_t jn = (a.m - j0 < (uint32_t)kPbarTile) ? (a.m - j0) : (uint32_t)kPbarTile;
+        __syncthreads();
+        for (uint32_t x = t; x < jn; x += kThreads) pb[x] = a.pbar[j0 + x];
+        __syncthreads();
+        // inner sums of 64 vectors, then added to the running sum: keeps fp32 chains short
+        for (uint32_t jb = 0; jb < jn; jb += 64) {
+            const uint32_t je = (jn - jb < 64u) ? (jn - jb) : 64u;
+            float acc[kReconBlocks][4];
+#pragma unroll
+            for (int r = 0; r < kReconBlocks; ++r)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[r][k] = 0.0f;
+            for (uint32_t jj = 0; jj < je; ++jj) {
+                const float p = pb[jb + jj];
+                const uint32_t j = j0 + jb + jj;
+#pragma unroll
+                for (int r = 0; r < kReconBlocks; ++r) {
+                    const uint32_t q = (uint32_t)(qbase + (uint64_t)r * kThreads);
+                    const Normals z = xi_block(q, j, a.r0, a.r1, a.k0, a.k1);
+                    acc[r][0] = fmaf(p, z.z0, acc[r][0]);
+                    acc[r][1] = fmaf(p, z.z1, acc[r][1]);
+                    acc[r][2] = fmaf(p, z.z2, acc[r][2]);
+                    acc[r][3] = fmaf(p, z.z3, acc[r][3]);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < kReconBlocks; ++r)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) outer[r][k] += acc[r][k];
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < kReconBlocks; ++r) {
+        const uint64_t q = qbase + (uint64_t)r * kThreads;
+        if (q >= nblk) continue;
+        const uint64_t i = 4 * q;
+        const float v0 = a.scale * outer[r][0], v1 = a.scale * outer[r][1];
+        const float v2 = a.scale * outer[r][2], v3 = a.scale * outer[r][3];
+        if (a.vec_store && i + 4 <= a.d) {
+            *reinterpret_cast<float4*>(a.gtilde + i) = make_float4(v0, v1, v2, v3);
+        } else {
+            if (i + 0 < a.d) a.gtilde[i + 0] = v0;
+            if (i + 1 < a.d) a.gtilde[i + 1] = v1;
+            if (i + 2 < a.d) a.gtilde[i + 2] = v2;
+            if (i + 3 < a.d) a.gtilde[i + 3] = v3;
+        }
+    }
+}
+
+// ---- test-only generator dumps ----------------------------------------------------------------
+
+__global__ void __launch_bounds__(kThreads) debug_philox_kernel(uint32_t k0, uint32_t k1, uint32_t r0,
+                                                                uint32_t r1, uint32_t j, uint64_t q0,
+                                                                uint64_t nblocks, uint32_t* out)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (b >= nblocks) return;
+    const Words w = philox4x32_10((uint32_t)(q0 + b), j, r0, r1, k0, k1);
+    out[4 * b + 0] = w.x0;
+    out[4 * b + 1] = w.x1;
+    out[4 * b + 2] = w.x2;
+    out[4 * b + 3] = w.x3;
+}
+
+__global__ void __launch_bounds__(kThreads) debug_xi_kernel(uint32_t k0, uint32_t k1, uint32_t r0,
+                                                            uint32_t r1, uint32_t j, uint64_t i0,
+                                                            uint64_t count, float* out)
+{
+    const uint64_t tt = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (tt >= count) return;
+    const uint64_t i = i0 + tt;
+    const Normals z = xi_block((uint32_t)(i >> 2), j, r0, r1, k0, k1);
+    const uint32_t k = (uint32_t)(i & 3u);
+    out[tt] = (k == 0) ? z.z0 : (k == 1) ? z.z1 : (k == 2) ? z.z2 : z.z3;
+}
+
+}  // namespace core

@@ -1,0 +1,108 @@
+"""Host-only checks of the C-ABI library: it loads, exports what include/core.h declares, and
+turns every bad argument into an error code before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2309_13307_amd as core
+from paper_2309_13307_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-null, 16-byte aligned "device pointer" that is never dereferenced on the host
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "core.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(core_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = core.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_strerror_covers_all_codes():
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5):
+        s = core.strerror(code)
+        assert s and s != core.strerror(-99)
+        seen.add(s)
+    assert len(seen) == 6
+
+
+def test_workspace_bytes():
+    assert core.core_workspace_bytes(0, 4, 2) == 0
+    assert core.core_workspace_bytes(16, 0, 2) == 0
+    assert core.core_workspace_bytes(16, 4, 0) == 0
+    assert core.core_workspace_bytes((1 << 34) + 1, 4, 1) == 0
+    assert core.core_workspace_bytes(16, 4, 70000) == 0
+    small = core.core_workspace_bytes(1024, 16, 4)
+    big = core.core_workspace_bytes(25_557_032, 1024, 8)
+    assert 0 < small < big < (1 << 30)
+    # deterministic in its arguments, monotone in n
+    assert big == core.core_workspace_bytes(25_557_032, 1024, 8)
+    assert core.core_workspace_bytes(25_557_032, 1024, 16) > big
+
+
+def _round(L, d=1024, m=16, n=4, G=FAKE, dt=0, ld=None, pbar=FAKE, gt=FAKE, ws=FAKE, wsb=None):
+    ld = d if ld is None else ld
+    wsb = core.core_workspace_bytes(d, m, n) if wsb is None else wsb
+    return L.core_round(1, 0, d, m, n, G, dt, ld, pbar, gt, ws, wsb, None)
+
+
+def test_invalid_arguments_are_rejected_before_any_launch():
+    L = core.load_library()
+    E = binding
+    assert _round(L, G=None) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, pbar=None) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, gt=None) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, ws=None) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, d=0, wsb=1 << 20) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, m=0, wsb=1 << 20) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, n=0, wsb=1 << 20) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, d=(1 << 34) + 4, wsb=1 << 20) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, ld=1023) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, dt=7) == E.ERR_INVALID_ARGUMENT
+    assert _round(L, G=FAKE + 2, dt=0) == E.ERR_MISALIGNED
+    assert _round(L, G=FAKE + 1, dt=1) == E.ERR_MISALIGNED
+    assert _round(L, pbar=FAKE + 2) == E.ERR_MISALIGNED
+    assert _round(L, gt=FAKE + 1) == E.ERR_MISALIGNED
+    assert _round(L, ws=FAKE + 8) == E.ERR_MISALIGNED
+    assert _round(L, wsb=core.core_workspace_bytes(1024, 16, 4) - 1) == E.ERR_WORKSPACE_TOO_SMALL
+    # the other entry points
+    assert L.core_compress(1, 0, 16, 4, None, 0, FAKE, FAKE, 1 << 20, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_compress(1, 0, 16, 4, FAKE, 0, None, FAKE, 1 << 20, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_compress(1, 0, 16, 4, FAKE, 0, FAKE, FAKE, 8, None) == E.ERR_WORKSPACE_TOO_SMALL
+    assert L.core_compress_batched(1, 0, 16, 4, 2, FAKE, 0, 15, None, FAKE, FAKE, 1 << 20, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_compress_batched(1, 0, 16, 4, 2, FAKE, 0, 16, FAKE + 2, FAKE, FAKE, 1 << 20, None) == E.ERR_MISALIGNED
+    assert L.core_reconstruct(1, 0, 16, 4, None, 0.25, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_reconstruct(1, 0, 16, 4, FAKE, 0.25, None, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_reconstruct(1, 0, 0, 4, FAKE, 0.25, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_reconstruct(1, 0, 16, 0, FAKE, 0.25, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_philox(1, 0, 0, 0, 0, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_philox(1, 0, 0, (1 << 32) - 1, 2, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_philox(1, 0, 0, 0, 4, None, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_xi(1, 0, 0, 0, 0, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_xi(1, 0, 0, (1 << 34) - 1, 2, FAKE, None) == E.ERR_INVALID_ARGUMENT
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a host without a GPU")
+def test_no_device_is_a_clean_error():
+    L = core.load_library()
+    assert _round(L) == binding.ERR_NO_DEVICE
+    assert L.core_reconstruct(1, 0, 16, 4, FAKE, 0.25, FAKE, None) == binding.ERR_NO_DEVICE
+    assert L.core_debug_xi(1, 0, 0, 0, 4, FAKE, None) == binding.ERR_NO_DEVICE
+
+
+def test_binding_refuses_host_tensors():
+    with pytest.raises(ValueError):
+        core.core_round(1, 0, torch.zeros((2, 8)), 4)
+    with pytest.raises(ValueError):
+        core.core_reconstruct(1, 0, 8, torch.zeros(4), 0.25)
