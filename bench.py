@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the CORE hot path on one MI355X.
+
+A step is one `core_round` (projection of n client gradients onto m common Gaussian vectors,
+cross-chunk sum + client mean, reconstruction) over one batch of synthetic gradients that is
+already resident in HBM.  The default workload is the ResNet-50-sized configuration
+(d = 25,557,032, m = 1024, n = 8, bf16 storage, fp32 arithmetic).
+
+Prints ONE JSON line with the whole-job throughput (projected coordinates per second,
+d*m*n / t), a roofline object for the dominant kernel and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2309_13307_amd as core  # noqa: E402
+from paper_2309_13307_amd import workloads  # noqa: E402
+
+# Peak of the plain vector ALU: 256 CUs x 4 SIMDs x 32 fp32 lanes per clock x 2.4 GHz.  It is the
+# published 157.3 TFLOP/s fp32 vector figure divided by the 2 flops of an FMA; measured on this
+# chip, a wave64 two-operand VALU instruction issues in ~2 cycles, i.e. 32 lanes per clock.
+PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
+
+# Algorithmic lane-operations per (coordinate, vector) pair: one Philox4x32-10 call is 20 wide
+# multiplies + 20 key/xor steps for 4 outputs -> 20 per output counting half-products and xors;
+# uniform map + Box-Muller ~6 per output; then n projection FMAs, or 1 reconstruction FMA.
+OPS_GENERATE = 26
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config4", choices=["config3", "config4", "config5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy (3x) and exit; used to scale "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a profiler run")
+    return ap.parse_args()
+
+
+def cpu_baseline(case, d_s=1 << 20, m_s=128):
+    """The oracle as it stands, one thread, on the first d_s coordinates x m_s vectors x all clients."""
+    import oracle
+    d_s = min(d_s, case.d)
+    m_s = min(m_s, case.m)
+    G_host = np.ascontiguousarray(workloads.to_host(case.G[:, :d_s]))
+    oracle.lib()
+    t0 = time.perf_counter()
+    oracle.core_round(case.seed, 0, G_host, m_s)
+    dt = time.perf_counter() - t0
+    return {
+        "value": d_s * m_s * case.n / dt,
+        "unit": "coords/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"one full oracle round on the first {d_s} coordinates x first {m_s} vectors x all "
+                  f"{case.n} clients of the same G ({dt:.1f} s)",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1.", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4,
+                          "launches": 3}))
+        return 0
+    core.load_library()
+
+    case = {"config3": workloads.config3, "config4": workloads.config4,
+            "config5": workloads.config5}[args.workload](dev)
+    d, m, n = case.d, case.m, case.n
+    G = case.G
+    ws = core.alloc_workspace(d, m, n, dev)
+    pbar = torch.empty(m, dtype=torch.float32, device=dev)
+    gtilde = torch.empty(d, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    rnd = 0
+    for _ in range(args.warmup):
+        core.core_round(case.seed, rnd, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
+        rnd += 1
+    torch.cuda.synchronize()
+
+    # timed region: exactly K rounds with distinct round counters
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        core.core_round(case.seed, rnd, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
+        rnd += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    units = float(d) * m * n
+    value = units / (elapsed / args.steps)
+
+    # per-kernel durations with events on the launch stream (the binding launches on torch's
+    # current stream).  core_round is exactly these two calls back to back.
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for k in range(args.steps):
+        ev[k][0].record()
+        core.core_compress_batched(case.seed, rnd, G, m, pbar=pbar, ws=ws, want_P=False)
+        ev[k][1].record()
+        core.core_reconstruct(case.seed, rnd, d, pbar, 1.0 / m, gtilde=gtilde)
+        ev[k][2].record()
+        rnd += 1
+    torch.cuda.synchronize()
+    t_proj = float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e-3
+    t_recon = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) * 1e-3
+
+    pairs = float(d) * m
+    ops_proj = pairs * (OPS_GENERATE + n)
+    ops_recon = pairs * (OPS_GENERATE + 1)
+    ach_proj = ops_proj / t_proj
+    ach_recon = ops_recon / t_recon
+    ach_round = (ops_proj + ops_recon) / (ms_per_step * 1e-3)
+    esize = 2 if G.dtype == torch.bfloat16 else 4
+    algo_bytes = float(n) * d * esize + 4.0 * d
+
+    out = {
+        "metric": "projected coords/sec (d*m*n/s) for compress+reconstruct",
+        "value": value,
+        "unit": "coords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{case.name}: one core_round, d={d}, m={m}, n={n}, G stored "
+                        f"{'bf16' if esize == 2 else 'fp32'}, fp32 arithmetic, inputs resident in HBM",
+            "d": d, "m": m, "n": n,
+        },
+        "pct_fp32_valu_peak": 100.0 * ach_round / PEAK_LANE_OPS,
+        "roofline": {
+            "bound": "alu",
+            "kernel": "project_kernel (core_compress_batched: projection + cross-chunk sum)",
+            "achieved": ach_proj / 1e12,
+            "peak": PEAK_LANE_OPS / 1e12,
+            "unit": "Tlaneop/s",
+            "frac": ach_proj / PEAK_LANE_OPS,
+            "traffic": None,
+            "ms": t_proj * 1e3,
+            "lane_ops_per_pair": OPS_GENERATE + n,
+            "second_kernel": {
+                "kernel": "reconstruct_kernel (core_reconstruct)",
+                "achieved": ach_recon / 1e12,
+                "frac": ach_recon / PEAK_LANE_OPS,
+                "ms": t_recon * 1e3,
+                "lane_ops_per_pair": OPS_GENERATE + 1,
+            },
+            "whole_round_frac": ach_round / PEAK_LANE_OPS,
+            "hbm_algorithmic_bytes": algo_bytes,
+            "hbm_achieved_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,
+            "hbm_peak_GBps": 8000.0,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
