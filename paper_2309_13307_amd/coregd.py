@@ -1,0 +1,60 @@
+"""CORE-GD (Algorithm 2 of arXiv 2309.13307) driver for a ridge-regression objective.
+
+The library covers the three communication lines of Algorithm 2 (`core_round`); this harness
+supplies what surrounds them on the device with torch: the client gradients
+g_c = n A_c^T (A_c x - b_c) + lam x of f_c(x) = n/2 |A_c x - b_c|^2 + lam/2 |x|^2 (so that
+f = (1/n) sum_c f_c = 1/2 |A x - b|^2 + lam/2 |x|^2, Eq. (problem)), and the update
+x <- x - h * gtilde (last line of the loop in Algorithm 2).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding
+
+
+def step_size(s: np.ndarray, lam: float, m: int) -> float:
+    """h = m / (3 tr(H) + 2 m L) for H = A^T A + lam I with singular values s of A.
+
+    This maximises the decrease h - h^2 (3 tr(A)/(2m) + L) in the proof of Theorem 4.2 before the
+    theorem specialises to m <= tr(A)/L (where it becomes Theta(m / tr(A)), the theorem's choice)."""
+    d = s.shape[0]
+    tr_h = float((s ** 2).sum() + d * lam)
+    big_l = float(s.max() ** 2 + lam)
+    return m / (3.0 * tr_h + 2.0 * m * big_l)
+
+
+class RidgeCoreGD:
+    """Holds A, b on the device and runs CORE-GD rounds through the C-ABI library."""
+
+    def __init__(self, A: np.ndarray, b: np.ndarray, lam: float, n: int, m: int, seed: int,
+                 device="cuda"):
+        rows, d = A.shape
+        assert rows % n == 0
+        self.A = torch.from_numpy(np.ascontiguousarray(A, dtype=np.float32)).to(device)
+        self.b = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(device)
+        self.A3 = self.A.view(n, rows // n, d)
+        self.lam, self.n, self.m, self.seed, self.d = lam, n, m, seed, d
+        self.x = torch.zeros(d, dtype=torch.float32, device=device)
+        self.ws = binding.alloc_workspace(d, m, n, device)
+        self.pbar = torch.empty(m, dtype=torch.float32, device=device)
+        self.gtilde = torch.empty(d, dtype=torch.float32, device=device)
+
+    def client_gradients(self) -> torch.Tensor:
+        r3 = (self.A @ self.x - self.b).view(self.n, -1, 1)
+        G = self.n * torch.bmm(self.A3.transpose(1, 2), r3).squeeze(-1) + self.lam * self.x
+        return G.contiguous()
+
+    def loss(self) -> float:
+        x = self.x.double()
+        r = self.A.double() @ x - self.b.double()
+        return float(0.5 * (r @ r) + 0.5 * self.lam * (x @ x))
+
+    def round(self, k: int, h: float, G: torch.Tensor | None = None) -> torch.Tensor:
+        """One round of Algorithm 2 with round counter k; returns the client gradients it used."""
+        if G is None:
+            G = self.client_gradients()
+        binding.core_round(self.seed, k, G, self.m, pbar=self.pbar, gtilde=self.gtilde, ws=self.ws)
+        self.x -= h * self.gtilde
+        return G

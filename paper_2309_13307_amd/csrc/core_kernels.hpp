@@ -77,6 +77,10 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
     uint64_t tile_end = tile_begin + a.tiles_per_chunk;
     if (tile_end > tiles_total) tile_end = tiles_total;
 
+    // lanes differ in j (counter word 1) only: the state is fully divergent after 3 rounds
+    Generator<3, 4> gen;
+    gen.init(a.k0, a.k1, a.r0, a.r1);
+
     float acc_outer[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) acc_outer[c] = 0.0f;
@@ -107,14 +111,15 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
         const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
 #pragma unroll 2
         for (int qq = 0; qq < kTile / 4; ++qq) {
-            const Normals z = xi_block(q0 + (uint32_t)qq, j, a.r0, a.r1, a.k0, a.k1);
+            float z0, z1, z2, z3;
+            gen.block(q0 + (uint32_t)qq, j, z0, z1, z2, z3);
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const float4 g = *reinterpret_cast<const float4*>(&tile[c][4 * qq]);
-                acc[c] = fmaf(z.z0, g.x, acc[c]);
-                acc[c] = fmaf(z.z1, g.y, acc[c]);
-                acc[c] = fmaf(z.z2, g.z, acc[c]);
-                acc[c] = fmaf(z.z3, g.w, acc[c]);
+                acc[c] = fmaf(z0, g.x, acc[c]);
+                acc[c] = fmaf(z1, g.y, acc[c]);
+                acc[c] = fmaf(z2, g.z, acc[c]);
+                acc[c] = fmaf(z3, g.w, acc[c]);
             }
         }
 #pragma unroll
@@ -125,7 +130,7 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             if ((uint32_t)c < a.nc)
-                a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + j] = acc_outer[c];
+                a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + j] = kXiScale * acc_outer[c];
         }
     }
 }
@@ -186,6 +191,10 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
     const uint64_t nblk = (a.d + 3) / 4;   // Philox blocks in the vector
     const uint64_t qbase = (uint64_t)blockIdx.x * (kThreads * kReconBlocks) + t;
 
+    // lanes differ in q (counter word 0) only: the state is fully divergent after 2-3 rounds
+    Generator<2, 3> gen;
+    gen.init(a.k0, a.k1, a.r0, a.r1);
+
     float outer[kReconBlocks][4];
 #pragma unroll
     for (int r = 0; r < kReconBlocks; ++r)
@@ -211,11 +220,12 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
 #pragma unroll
                 for (int r = 0; r < kReconBlocks; ++r) {
                     const uint32_t q = (uint32_t)(qbase + (uint64_t)r * kThreads);
-                    const Normals z = xi_block(q, j, a.r0, a.r1, a.k0, a.k1);
-                    acc[r][0] = fmaf(p, z.z0, acc[r][0]);
-                    acc[r][1] = fmaf(p, z.z1, acc[r][1]);
-                    acc[r][2] = fmaf(p, z.z2, acc[r][2]);
-                    acc[r][3] = fmaf(p, z.z3, acc[r][3]);
+                    float z0, z1, z2, z3;
+                    gen.block(q, j, z0, z1, z2, z3);
+                    acc[r][0] = fmaf(p, z0, acc[r][0]);
+                    acc[r][1] = fmaf(p, z1, acc[r][1]);
+                    acc[r][2] = fmaf(p, z2, acc[r][2]);
+                    acc[r][3] = fmaf(p, z3, acc[r][3]);
                 }
             }
 #pragma unroll
@@ -230,8 +240,9 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
         const uint64_t q = qbase + (uint64_t)r * kThreads;
         if (q >= nblk) continue;
         const uint64_t i = 4 * q;
-        const float v0 = a.scale * outer[r][0], v1 = a.scale * outer[r][1];
-        const float v2 = a.scale * outer[r][2], v3 = a.scale * outer[r][3];
+        const float sc = a.scale * kXiScale;
+        const float v0 = sc * outer[r][0], v1 = sc * outer[r][1];
+        const float v2 = sc * outer[r][2], v3 = sc * outer[r][3];
         if (a.vec_store && i + 4 <= a.d) {
             *reinterpret_cast<float4*>(a.gtilde + i) = make_float4(v0, v1, v2, v3);
         } else {
@@ -251,7 +262,9 @@ __global__ void __launch_bounds__(kThreads) debug_philox_kernel(uint32_t k0, uin
 {
     const uint64_t b = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
     if (b >= nblocks) return;
-    const Words w = philox4x32_10((uint32_t)(q0 + b), j, r0, r1, k0, k1);
+    Generator<10, 10> gen;
+    gen.init(k0, k1, r0, r1);
+    const Words w = gen.words((uint32_t)(q0 + b), j);
     out[4 * b + 0] = w.x0;
     out[4 * b + 1] = w.x1;
     out[4 * b + 2] = w.x2;
@@ -265,9 +278,12 @@ __global__ void __launch_bounds__(kThreads) debug_xi_kernel(uint32_t k0, uint32_
     const uint64_t tt = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
     if (tt >= count) return;
     const uint64_t i = i0 + tt;
-    const Normals z = xi_block((uint32_t)(i >> 2), j, r0, r1, k0, k1);
+    Generator<4, 4> gen;
+    gen.init(k0, k1, r0, r1);
+    float z0, z1, z2, z3;
+    gen.block((uint32_t)(i >> 2), j, z0, z1, z2, z3);
     const uint32_t k = (uint32_t)(i & 3u);
-    out[tt] = (k == 0) ? z.z0 : (k == 1) ? z.z1 : (k == 2) ? z.z2 : z.z3;
+    out[tt] = kXiScale * ((k == 0) ? z0 : (k == 1) ? z1 : (k == 2) ? z2 : z3);
 }
 
 }  // namespace core

@@ -1,0 +1,75 @@
+"""Config 2: CORE-GD (Algorithm 2) on synthetic ridge regression, 200 rounds, d = 4096, m = 64,
+n = 8, with the round done by the HIP library and the gradients / update by the torch harness.
+
+Checks, per the paper: every sampled round's (pbar, gtilde) against the oracle fed the same
+client gradients; the loss curve against the oracle's own fp64 run of Algorithm 2 from the same
+start; the loss gap to the closed-form minimiser x* = (A^T A + lam I)^-1 A^T b shrinking at least
+as fast as the bound that follows from the proof of Theorem 4.2 for the step used, within
+Monte-Carlo slack (one trajectory)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import coregd as ocoregd
+import paper_2309_13307_amd as core
+from paper_2309_13307_amd import coregd, workloads
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.timeout(400)
+def test_config2_core_gd_ridge():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    _say("config2: building the ridge problem (QR of an 8192x4096 Gaussian; ~20 s)")
+    pr = workloads.ridge_problem()
+    d = pr.A.shape[1]
+    s = 1.0 / np.arange(1, d + 1)
+    h = coregd.step_size(s, pr.lam, pr.m)
+    A64, b64 = pr.A.astype(np.float64), pr.b.astype(np.float64)
+    xs = ocoregd.ridge_solution(A64, b64, pr.lam)
+    fstar = ocoregd.ridge_loss(A64, b64, pr.lam, xs)
+
+    _say("config2: 200 rounds on the GPU")
+    run = coregd.RidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed)
+    gaps = [run.loss() - fstar]
+    sampled = set([0, 1, 2, 199] + list(range(10, 200, 10)))
+    for k in range(pr.rounds):
+        G = run.round(k, h)
+        if k in sampled:
+            torch.cuda.synchronize()
+            G_host = G.cpu().numpy()
+            P_ref, pbar_ref, gt_ref = oracle.core_round(pr.seed, k, G_host, pr.m)
+            norms = parity.row_norms(G_host)
+            parity.check_projections(run.pbar.cpu().numpy()[None, :], pbar_ref[None, :],
+                                     np.array([norms.mean()]), d, pr.m, f"round {k} pbar")
+            parity.check_gtilde(run.gtilde.cpu().numpy(), gt_ref, f"round {k} gtilde")
+        gaps.append(run.loss() - fstar)
+    gaps = np.array(gaps)
+
+    _say("config2: the oracle's own 200 rounds (fp64)")
+    x_ref, losses_ref = ocoregd.core_gd(A64, b64, pr.lam, pr.n, pr.m, h, pr.rounds, pr.seed)
+    gaps_ref = losses_ref - fstar
+    print("round   gap(GPU path)   gap(oracle)")
+    for k in (0, 1, 2, 5, 10, 20, 50, 100, 150, 200):
+        print(f"{k:5d}   {gaps[k]:.6e}   {gaps_ref[k]:.6e}")
+    # fp32 gradients and an fp32 iterate against an all-fp64 run: the two curves stay together
+    assert np.all(np.abs(gaps - gaps_ref) <= 2e-3 * gaps_ref + 1e-7)
+    x_gpu = run.x.double().cpu().numpy()
+    assert np.linalg.norm(x_gpu - x_ref) <= 1e-3 * np.linalg.norm(x_ref)
+    # progress against the closed-form optimum
+    assert gaps[-1] < 0.15 * gaps[0]
+    assert np.all(gaps > 0)
+    # expected contraction per round for this step is at most 1 - mu h (proof of Theorem 4.2 with
+    # the strong-convexity step); one trajectory, so allow slack on the exponent
+    mu = float(s.min() ** 2 + pr.lam)
+    assert gaps[-1] <= gaps[0] * (1.0 - mu * h) ** (0.5 * pr.rounds)
