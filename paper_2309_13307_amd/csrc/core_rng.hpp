@@ -69,8 +69,11 @@ struct Generator {
             const uint32_t k1 = (r >= kVecFrom1) ? kv[r][1] : ks1 + (uint32_t)r * kPhiloxW1;
             const uint64_t pa = (uint64_t)c0 * kPhiloxM0;
             const uint64_t pb = (uint64_t)c2 * kPhiloxM1;
-            const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-            const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+            // three-way xor: one v_bitop3_b32 (truth table 0x96) once all three inputs are divergent
+            const uint32_t n0 = (r >= kVecFrom0) ? __builtin_amdgcn_bitop3_b32((uint32_t)(pb >> 32), c1, k0, 0x96)
+                                                 : (uint32_t)(pb >> 32) ^ c1 ^ k0;
+            const uint32_t n2 = (r >= kVecFrom1) ? __builtin_amdgcn_bitop3_b32((uint32_t)(pa >> 32), c3, k1, 0x96)
+                                                 : (uint32_t)(pa >> 32) ^ c3 ^ k1;
             c1 = (uint32_t)pb;
             c3 = (uint32_t)pa;
             c0 = n0;
