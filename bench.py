@@ -45,6 +45,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config4", choices=["config3", "config4", "config5"])
+    ap.add_argument("--variant", default="regenerate", choices=["regenerate", "materialized"],
+                    help="materialized = the comparison variant that stores Xi while projecting and "
+                         "reads it back to reconstruct (needs 4*d*m bytes of HBM)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (3x) and exit; used to scale "
@@ -102,18 +105,26 @@ def main():
     ws = core.alloc_workspace(d, m, n, dev)
     pbar = torch.empty(m, dtype=torch.float32, device=dev)
     gtilde = torch.empty(d, dtype=torch.float32, device=dev)
+    mat = args.variant == "materialized"
+    xi = core.alloc_xi(d, m, dev) if mat else None
     torch.cuda.synchronize()
+
+    def one_round(r):
+        if mat:
+            core.core_round_materialized(case.seed, r, G, m, xi, pbar=pbar, gtilde=gtilde, ws=ws)
+        else:
+            core.core_round(case.seed, r, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
 
     rnd = 0
     for _ in range(args.warmup):
-        core.core_round(case.seed, rnd, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
+        one_round(rnd)
         rnd += 1
     torch.cuda.synchronize()
 
     # timed region: exactly K rounds with distinct round counters
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        core.core_round(case.seed, rnd, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
+        one_round(rnd)
         rnd += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -126,9 +137,14 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for k in range(args.steps):
         ev[k][0].record()
-        core.core_compress_batched(case.seed, rnd, G, m, pbar=pbar, ws=ws, want_P=False)
-        ev[k][1].record()
-        core.core_reconstruct(case.seed, rnd, d, pbar, 1.0 / m, gtilde=gtilde)
+        if mat:
+            _, pb = core.core_compress_batched_store_xi(case.seed, rnd, G, m, xi, ws=ws, want_P=False)
+            ev[k][1].record()
+            core.core_reconstruct_from_xi(d, pb, 1.0 / m, xi, gtilde=gtilde)
+        else:
+            core.core_compress_batched(case.seed, rnd, G, m, pbar=pbar, ws=ws, want_P=False)
+            ev[k][1].record()
+            core.core_reconstruct(case.seed, rnd, d, pbar, 1.0 / m, gtilde=gtilde)
         ev[k][2].record()
         rnd += 1
     torch.cuda.synchronize()
@@ -160,7 +176,7 @@ def main():
         "config": {
             "workload": f"{case.name}: one core_round, d={d}, m={m}, n={n}, G stored "
                         f"{'bf16' if esize == 2 else 'fp32'}, fp32 arithmetic, inputs resident in HBM",
-            "d": d, "m": m, "n": n,
+            "d": d, "m": m, "n": n, "variant": args.variant,
         },
         "pct_fp32_valu_peak": 100.0 * ach_round / PEAK_LANE_OPS,
         "roofline": {

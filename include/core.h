@@ -114,6 +114,34 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
                float *pbar, float *gtilde,
                void *ws, size_t ws_bytes, core_stream stream);
 
+/* ---- materialised-Xi comparison variant ---------------------------------------------------
+ * The matrix Xi = [xi_1 ... xi_m]^T of the paper's privacy appendix (p = Xi a) is normally never
+ * stored.  These entry points store it once, while projecting, and read it back to reconstruct,
+ * so that "generate twice" can be measured against "generate once + 8 bytes of HBM traffic per
+ * normal".  Layout of xi: [ceil(d/4)][m][4] fp32, xi[q][j][k] = xi_j[4q+k]; entries with
+ * 4q+k >= d are written but never used.  xi must be 16-byte aligned and hold
+ * core_xi_bytes(d, m) bytes (0 = sizes out of range); it is caller-owned device memory. */
+size_t core_xi_bytes(uint64_t d, uint32_t m);
+
+/* core_compress_batched that also writes xi (outputs: P (may be NULL), pbar, xi). */
+int core_compress_batched_store_xi(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                                   const void *G, core_dtype dt, uint64_t ld,
+                                   float *P, float *pbar,
+                                   float *xi, size_t xi_buf_bytes,
+                                   void *ws, size_t ws_bytes, core_stream stream);
+
+/* Eq. (reconstruction) from a stored xi: gtilde[i] = scale * sum_j pbar[j] xi_j[i]. */
+int core_reconstruct_from_xi(uint64_t d, uint32_t m, const float *pbar, float scale,
+                             const float *xi, size_t xi_buf_bytes,
+                             float *gtilde, core_stream stream);
+
+/* core_round through the stored xi (same outputs as core_round; xi is scratch). */
+int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                            const void *G, core_dtype dt, uint64_t ld,
+                            float *pbar, float *gtilde,
+                            float *xi, size_t xi_buf_bytes,
+                            void *ws, size_t ws_bytes, core_stream stream);
+
 /* ---- test-only exports: raw generator output -------------------------------- */
 
 /* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks.  out device uint32. */

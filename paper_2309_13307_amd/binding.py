@@ -26,6 +26,8 @@ ERR_NO_DEVICE = -5
 EXPORTS = (
     "core_strerror", "core_last_hip_error", "core_workspace_bytes", "core_compress",
     "core_compress_batched", "core_reconstruct", "core_round", "core_debug_philox", "core_debug_xi",
+    "core_xi_bytes", "core_compress_batched_store_xi", "core_reconstruct_from_xi",
+    "core_round_materialized",
 )
 
 
@@ -62,6 +64,15 @@ def load_library() -> ctypes.CDLL:
     L.core_reconstruct.restype = i32
     L.core_round.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz, vp]
     L.core_round.restype = i32
+    L.core_xi_bytes.argtypes = [u64, u32]
+    L.core_xi_bytes.restype = sz
+    L.core_compress_batched_store_xi.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz,
+                                                 vp, sz, vp]
+    L.core_compress_batched_store_xi.restype = i32
+    L.core_reconstruct_from_xi.argtypes = [u64, u32, vp, f32, vp, sz, vp, vp]
+    L.core_reconstruct_from_xi.restype = i32
+    L.core_round_materialized.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz, vp, sz, vp]
+    L.core_round_materialized.restype = i32
     L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     L.core_debug_philox.restype = i32
     L.core_debug_xi.argtypes = [u64, u64, u32, u64, u64, vp, vp]
@@ -183,6 +194,74 @@ def core_round(seed: int, rnd: int, G: torch.Tensor, m: int, d: int | None = Non
                                    pbar.data_ptr(), gtilde.data_ptr(), ws.data_ptr(), ws.numel(),
                                    _stream())
     _check(rc, "core_round")
+    return pbar, gtilde
+
+
+def core_xi_bytes(d: int, m: int) -> int:
+    return int(load_library().core_xi_bytes(d, m))
+
+
+def alloc_xi(d: int, m: int, device="cuda") -> torch.Tensor:
+    """Buffer for the materialised-Xi comparison variant, viewed as [ceil(d/4), m, 4] fp32."""
+    nbytes = core_xi_bytes(d, m)
+    if nbytes == 0:
+        raise CoreError(ERR_INVALID_ARGUMENT, "core_xi_bytes")
+    return torch.empty((nbytes // (16 * m), m, 4), dtype=torch.float32, device=device)
+
+
+def core_compress_batched_store_xi(seed: int, rnd: int, G: torch.Tensor, m: int, xi: torch.Tensor,
+                                   d: int | None = None, ws: torch.Tensor | None = None,
+                                   want_P: bool = True):
+    """core_compress_batched that also writes the normals it generates into `xi`."""
+    _require_cuda(G, xi, ws)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    P = torch.empty((n, m), dtype=torch.float32, device=G.device) if want_P else None
+    pbar = torch.empty(m, dtype=torch.float32, device=G.device)
+    if ws is None:
+        ws = alloc_workspace(d, m, n, G.device)
+    rc = load_library().core_compress_batched_store_xi(
+        seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld, P.data_ptr() if P is not None else None,
+        pbar.data_ptr(), xi.data_ptr(), xi.numel() * 4, ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "core_compress_batched_store_xi")
+    return P, pbar
+
+
+def core_reconstruct_from_xi(d: int, pbar: torch.Tensor, scale: float, xi: torch.Tensor,
+                             gtilde: torch.Tensor | None = None) -> torch.Tensor:
+    _require_cuda(pbar, xi, gtilde)
+    m = pbar.numel()
+    if gtilde is None:
+        gtilde = torch.empty(d, dtype=torch.float32, device=pbar.device)
+    rc = load_library().core_reconstruct_from_xi(d, m, pbar.data_ptr(), scale, xi.data_ptr(),
+                                                 xi.numel() * 4, gtilde.data_ptr(), _stream())
+    _check(rc, "core_reconstruct_from_xi")
+    return gtilde
+
+
+def core_round_materialized(seed: int, rnd: int, G: torch.Tensor, m: int, xi: torch.Tensor,
+                            d: int | None = None, pbar: torch.Tensor | None = None,
+                            gtilde: torch.Tensor | None = None, ws: torch.Tensor | None = None):
+    """core_round that stores Xi while projecting and reads it back to reconstruct."""
+    _require_cuda(G, xi, pbar, gtilde, ws)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    if pbar is None:
+        pbar = torch.empty(m, dtype=torch.float32, device=G.device)
+    if gtilde is None:
+        gtilde = torch.empty(d, dtype=torch.float32, device=G.device)
+    if ws is None:
+        ws = alloc_workspace(d, m, n, G.device)
+    rc = load_library().core_round_materialized(
+        seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld, pbar.data_ptr(), gtilde.data_ptr(),
+        xi.data_ptr(), xi.numel() * 4, ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "core_round_materialized")
     return pbar, gtilde
 
 

@@ -71,10 +71,16 @@ int check_device()
 bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 template <int NC>
-hipError_t launch_project(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+hipError_t launch_project(const ProjectArgs& a, bool bf16, bool store_xi, uint32_t blocks, hipStream_t st)
 {
-    if (bf16) hipLaunchKernelGGL((project_kernel<NC, true>), dim3(blocks), dim3(kThreads), 0, st, a);
-    else      hipLaunchKernelGGL((project_kernel<NC, false>), dim3(blocks), dim3(kThreads), 0, st, a);
+    const dim3 g(blocks), b(kThreads);
+    if (store_xi) {
+        if (bf16) hipLaunchKernelGGL((project_kernel<NC, true, true>), g, b, 0, st, a);
+        else      hipLaunchKernelGGL((project_kernel<NC, false, true>), g, b, 0, st, a);
+    } else {
+        if (bf16) hipLaunchKernelGGL((project_kernel<NC, true, false>), g, b, 0, st, a);
+        else      hipLaunchKernelGGL((project_kernel<NC, false, false>), g, b, 0, st, a);
+    }
     return hipGetLastError();
 }
 
@@ -101,7 +107,7 @@ int validate_reconstruct(uint64_t d, uint32_t m, const float* pbar, const float*
 
 int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
                      const void* G, core_dtype dt, uint64_t ld, float* P, float* pbar,
-                     void* ws, const Plan& plan, hipStream_t st)
+                     void* ws, const Plan& plan, hipStream_t st, float* xi_store = nullptr)
 {
     char* base = (char*)ws;
     float* part = (float*)(base + plan.part_off);
@@ -113,18 +119,20 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
     a.jtiles = plan.jtiles; a.nchunks = plan.nchunks; a.tiles_per_chunk = plan.tiles_per_chunk;
     a.part = part;
+    a.xi_store = xi_store;
     const uint32_t blocks = (uint32_t)(ceil_div(plan.nchunks, 8) * 8 * plan.jtiles);
     const bool bf16 = (dt == CORE_DTYPE_BF16);
 
     for (uint32_t c0 = 0; c0 < n; c0 += kMaxClientsPerPass) {
         const uint32_t nc = (n - c0 < kMaxClientsPerPass) ? (n - c0) : kMaxClientsPerPass;
         a.c0 = c0; a.nc = nc;
+        const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
         hipError_t e;
-        if (nc <= 1)      e = launch_project<1>(a, bf16, blocks, st);
-        else if (nc <= 2) e = launch_project<2>(a, bf16, blocks, st);
-        else if (nc <= 4) e = launch_project<4>(a, bf16, blocks, st);
-        else if (nc <= 8) e = launch_project<8>(a, bf16, blocks, st);
-        else              e = launch_project<16>(a, bf16, blocks, st);
+        if (nc <= 1)      e = launch_project<1>(a, bf16, store, blocks, st);
+        else if (nc <= 2) e = launch_project<2>(a, bf16, store, blocks, st);
+        else if (nc <= 4) e = launch_project<4>(a, bf16, store, blocks, st);
+        else if (nc <= 8) e = launch_project<8>(a, bf16, store, blocks, st);
+        else              e = launch_project<16>(a, bf16, store, blocks, st);
         if (e != hipSuccess) return hip_fail(e);
     }
 
@@ -154,6 +162,27 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     return CORE_OK;
+}
+
+int enqueue_reconstruct_xi(uint64_t d, uint32_t m, const float* pbar, float scale, const float* xi,
+                           float* gtilde, hipStream_t st)
+{
+    ReconXiArgs a;
+    a.pbar = pbar; a.xi = xi; a.gtilde = gtilde; a.d = d; a.m = m; a.scale = scale;
+    const uint64_t nblk = ceil_div(d, 4);
+    hipLaunchKernelGGL(reconstruct_xi_kernel, dim3((uint32_t)ceil_div(nblk, kThreads / 64)), dim3(kThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
+}
+
+// bytes of the materialised Xi for (d, m); 0 if it cannot be addressed
+size_t xi_bytes(uint64_t d, uint32_t m)
+{
+    if (d == 0 || d > kMaxD || m == 0) return 0;
+    const uint64_t nblk = ceil_div(d, 4);
+    if (nblk > (~(uint64_t)0) / 16 / m) return 0;
+    if (ceil_div(nblk, kThreads / 64) > 0x7fffffffull) return 0;
+    return (size_t)(nblk * m * 16);
 }
 
 }  // namespace
@@ -221,6 +250,58 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
     rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
     if (rc != CORE_OK) return rc;
     return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream);
+}
+
+size_t core_xi_bytes(uint64_t d, uint32_t m) { return xi_bytes(d, m); }
+
+int core_compress_batched_store_xi(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                                   const void* G, core_dtype dt, uint64_t ld, float* P, float* pbar,
+                                   float* xi, size_t xi_buf_bytes, void* ws, size_t ws_bytes,
+                                   core_stream stream)
+{
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, P, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if (!xi) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(xi, 16)) return CORE_ERR_MISALIGNED;
+    const size_t need = xi_bytes(d, m);
+    if (need == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (xi_buf_bytes < need) return CORE_ERR_WORKSPACE_TOO_SMALL;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    return enqueue_compress(seed, round, d, m, n, G, dt, ld, P, pbar, ws, plan, (hipStream_t)stream, xi);
+}
+
+int core_reconstruct_from_xi(uint64_t d, uint32_t m, const float* pbar, float scale, const float* xi,
+                             size_t xi_buf_bytes, float* gtilde, core_stream stream)
+{
+    int rc = validate_reconstruct(d, m, pbar, gtilde);
+    if (rc != CORE_OK) return rc;
+    if (!xi) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(xi, 16)) return CORE_ERR_MISALIGNED;
+    const size_t need = xi_bytes(d, m);
+    if (need == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (xi_buf_bytes < need) return CORE_ERR_WORKSPACE_TOO_SMALL;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    return enqueue_reconstruct_xi(d, m, pbar, scale, xi, gtilde, (hipStream_t)stream);
+}
+
+int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                            const void* G, core_dtype dt, uint64_t ld, float* pbar, float* gtilde,
+                            float* xi, size_t xi_buf_bytes, void* ws, size_t ws_bytes, core_stream stream)
+{
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = validate_reconstruct(d, m, pbar, gtilde)) != CORE_OK) return rc;
+    if (!xi) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(xi, 16)) return CORE_ERR_MISALIGNED;
+    const size_t need = xi_bytes(d, m);
+    if (need == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (xi_buf_bytes < need) return CORE_ERR_WORKSPACE_TOO_SMALL;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream, xi);
+    if (rc != CORE_OK) return rc;
+    return enqueue_reconstruct_xi(d, m, pbar, 1.0f / (float)m, xi, gtilde, (hipStream_t)stream);
 }
 
 int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,

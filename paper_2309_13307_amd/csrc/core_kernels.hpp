@@ -43,6 +43,7 @@ struct ProjectArgs {
     uint32_t nchunks;     // chunks of d
     uint32_t tiles_per_chunk;
     float* part;          // [nchunks][n][m]
+    float* xi_store;      // materialised variant only: [ceil(d/4)][m][4], else unused
 };
 
 template <bool BF16>
@@ -55,7 +56,10 @@ __device__ __forceinline__ float load_g(const void* G, uint64_t idx)
     }
 }
 
-template <int NC, bool BF16>
+// STORE_XI: the materialised-Xi comparison variant.  The kernel additionally writes every normal
+// it generates to xi_store[q][j][0..3] = xi_j[4q..4q+3], so that reconstruct_xi_kernel can read
+// them back instead of regenerating them.
+template <int NC, bool BF16, bool STORE_XI = false>
 __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
 {
     __shared__ __attribute__((aligned(16))) float tile[NC][kTile];
@@ -113,6 +117,12 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
         for (int qq = 0; qq < kTile / 4; ++qq) {
             float z0, z1, z2, z3;
             gen.block(q0 + (uint32_t)qq, j, z0, z1, z2, z3);
+            if constexpr (STORE_XI) {
+                const uint64_t q = (uint64_t)q0 + (uint32_t)qq;
+                if (j < a.m && 4 * q < a.d)
+                    *reinterpret_cast<float4*>(a.xi_store + (q * a.m + j) * 4) =
+                        make_float4(kXiScale * z0, kXiScale * z1, kXiScale * z2, kXiScale * z3);
+            }
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const float4 g = *reinterpret_cast<const float4*>(&tile[c][4 * qq]);
@@ -251,6 +261,46 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
             if (i + 2 < a.d) a.gtilde[i + 2] = v2;
             if (i + 3 < a.d) a.gtilde[i + 3] = v3;
         }
+    }
+}
+
+// Materialised-Xi comparison variant of the reconstruction: gtilde[4q+k] = scale * sum_j pbar[j] *
+// xi[q][j][k] with the normals read back from memory (Xi = [xi_1 ... xi_m]^T of the privacy
+// appendix, stored in 4-coordinate blocks).  One wave per Philox block q, lanes over j
+// (coalesced 1 KB reads), then a wave butterfly; HBM-bound by construction (16 bytes per 4 pairs).
+struct ReconXiArgs {
+    const float* pbar;
+    const float* xi;      // [ceil(d/4)][m][4]
+    float* gtilde;
+    uint64_t d;
+    uint32_t m;
+    float scale;
+};
+
+__global__ void __launch_bounds__(kThreads) reconstruct_xi_kernel(ReconXiArgs a)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t q = (uint64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const uint64_t nblk = (a.d + 3) / 4;
+    if (q >= nblk) return;   // whole wave leaves together
+    const float4* row = reinterpret_cast<const float4*>(a.xi) + q * a.m;
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    for (uint32_t j = lane; j < a.m; j += 64) {
+        const float4 v = row[j];
+        const float p = a.pbar[j];
+        s0 = fmaf(p, v.x, s0); s1 = fmaf(p, v.y, s1); s2 = fmaf(p, v.z, s2); s3 = fmaf(p, v.w, s3);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        s0 += __shfl_xor(s0, off); s1 += __shfl_xor(s1, off);
+        s2 += __shfl_xor(s2, off); s3 += __shfl_xor(s3, off);
+    }
+    if (lane == 0) {
+        const uint64_t i = 4 * q;
+        if (i + 0 < a.d) a.gtilde[i + 0] = a.scale * s0;
+        if (i + 1 < a.d) a.gtilde[i + 1] = a.scale * s1;
+        if (i + 2 < a.d) a.gtilde[i + 2] = a.scale * s2;
+        if (i + 3 < a.d) a.gtilde[i + 3] = a.scale * s3;
     }
 }
 

@@ -106,3 +106,25 @@ def test_binding_refuses_host_tensors():
         core.core_round(1, 0, torch.zeros((2, 8)), 4)
     with pytest.raises(ValueError):
         core.core_reconstruct(1, 0, 8, torch.zeros(4), 0.25)
+
+
+def test_materialised_variant_arguments():
+    L = core.load_library()
+    E = binding
+    assert core.core_xi_bytes(0, 4) == 0 and core.core_xi_bytes(16, 0) == 0
+    assert core.core_xi_bytes(5, 3) == 2 * 3 * 16
+    assert core.core_xi_bytes(1 << 20, 256) == (1 << 18) * 256 * 16
+    wsb = core.core_workspace_bytes(1024, 16, 4)
+    xb = core.core_xi_bytes(1024, 16)
+    f = L.core_round_materialized
+    assert f(1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE, FAKE, None, xb, FAKE, wsb, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE, FAKE, FAKE + 4, xb, FAKE, wsb, None) == E.ERR_MISALIGNED
+    assert f(1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE, FAKE, FAKE, xb - 1, FAKE, wsb, None) == E.ERR_WORKSPACE_TOO_SMALL
+    assert f(1, 0, 1024, 16, 4, None, 0, 1024, FAKE, FAKE, FAKE, xb, FAKE, wsb, None) == E.ERR_INVALID_ARGUMENT
+    g = L.core_reconstruct_from_xi
+    assert g(1024, 16, FAKE, 0.1, None, xb, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert g(1024, 16, FAKE, 0.1, FAKE, xb - 16, FAKE, None) == E.ERR_WORKSPACE_TOO_SMALL
+    assert g(1024, 16, None, 0.1, FAKE, xb, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    h = L.core_compress_batched_store_xi
+    assert h(1, 0, 1024, 16, 4, FAKE, 0, 1024, None, FAKE, FAKE, xb, FAKE, wsb - 1, None) == E.ERR_WORKSPACE_TOO_SMALL
+    assert h(1, 0, 1024, 16, 4, FAKE, 0, 1024, None, FAKE, None, xb, FAKE, wsb, None) == E.ERR_INVALID_ARGUMENT

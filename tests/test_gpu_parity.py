@@ -200,3 +200,38 @@ def test_config3_full():
     case = workloads.config3(DEV)
     _say("config3 d=2^20 m=256 n=8 fp32 (oracle takes ~20 s)")
     _run_and_check(case.seed, 0, case.G, case.m, what="config3")
+
+
+@pytest.mark.parametrize("d,m,n,bf16", [(5, 2, 1, False), (1030, 70, 3, False), (20001, 300, 8, True),
+                                          (4096, 64, 20, False)])
+def test_materialised_xi_variant(d, m, n, bf16):
+    """The stored Xi holds the oracle's normals, and the round through it meets the same bars."""
+    _say(f"materialised d={d} m={m} n={n} bf16={bf16}")
+    rng = np.random.default_rng(d + m + n)
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
+    if bf16:
+        G = G.to(torch.bfloat16)
+    G_host = workloads.to_host(G)
+    P_ref, pbar_ref, gt_ref = oracle.core_round(19, 3, G_host, m)
+    xi = core.alloc_xi(d, m)
+    xi.fill_(float("nan"))
+    P, pbar = core.core_compress_batched_store_xi(19, 3, G, m, xi)
+    gt_from = core.core_reconstruct_from_xi(d, pbar, 1.0 / m, xi)
+    xi2 = core.alloc_xi(d, m)
+    pbar2, gt = core.core_round_materialized(19, 3, G, m, xi2)
+    pbar3, gt3 = core.core_round(19, 3, G, m)
+    _sync()
+    # stored normals against the oracle, entry by entry on sampled vectors
+    xi_h = xi.cpu().numpy()
+    for j in sorted(set([0, m - 1, m // 2])):
+        ref = oracle.xi_range(19, 3, j, 0, d)
+        got = xi_h[:, j, :].reshape(-1)[:d].astype(np.float64)
+        assert np.abs(got - ref).max() <= parity.XI_MAX_ABS
+    assert torch.equal(xi, xi2)
+    norms = parity.row_norms(G_host)
+    parity.check_projections(P.cpu().numpy(), P_ref, norms, d, m, "materialised P")
+    assert torch.equal(pbar, pbar2) and torch.equal(pbar, pbar3)
+    parity.check_gtilde(gt.cpu().numpy(), gt_ref, "materialised end-to-end")
+    assert torch.equal(gt, gt_from)
+    # and it agrees with the regenerating path to fp32 rounding
+    assert parity.rel_l2(gt.cpu().numpy(), gt3.cpu().numpy()) < 2e-6
