@@ -2,6 +2,8 @@
 // and kernel launches.  Nothing here touches device memory from the host or synchronises.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "../../include/core.h"
 #include "core_kernels.hpp"
@@ -84,6 +86,26 @@ hipError_t launch_project(const ProjectArgs& a, bool bf16, bool store_xi, uint32
     return hipGetLastError();
 }
 
+template <int NG>
+hipError_t launch_project_mfma(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+{
+    const dim3 g(blocks), b(kThreads);
+    if (bf16) hipLaunchKernelGGL((project_mfma_kernel<NG, true>), g, b, 0, st, a);
+    else      hipLaunchKernelGGL((project_mfma_kernel<NG, false>), g, b, 0, st, a);
+    return hipGetLastError();
+}
+
+// Which projection kernel serves a pass of nc clients.  Measured on MI355X (config 5, n = 16):
+// the matrix-pipe kernel is ~4 % faster than the VALU kernel at 16 clients and ~5 % slower at 8,
+// so it is the default above 8 clients.  CORE_PROJECT_VARIANT=valu|mfma forces one for A/B runs.
+bool use_mfma_projection(uint32_t nc)
+{
+    const char* v = getenv("CORE_PROJECT_VARIANT");
+    if (v && strcmp(v, "mfma") == 0) return true;
+    if (v && strcmp(v, "valu") == 0) return false;
+    return nc > 8;
+}
+
 int validate_compress(uint64_t d, uint32_t m, uint32_t n, const void* G, core_dtype dt, uint64_t ld,
                       const float* P, const float* pbar, const void* ws, size_t ws_bytes, Plan& plan)
 {
@@ -128,6 +150,12 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         a.c0 = c0; a.nc = nc;
         const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
         hipError_t e;
+        if (!store && use_mfma_projection(nc)) {
+            if (nc <= 4)       e = launch_project_mfma<1>(a, bf16, blocks, st);
+            else if (nc <= 8)  e = launch_project_mfma<2>(a, bf16, blocks, st);
+            else if (nc <= 12) e = launch_project_mfma<3>(a, bf16, blocks, st);
+            else               e = launch_project_mfma<4>(a, bf16, blocks, st);
+        } else
         if (nc <= 1)      e = launch_project<1>(a, bf16, store, blocks, st);
         else if (nc <= 2) e = launch_project<2>(a, bf16, store, blocks, st);
         else if (nc <= 4) e = launch_project<4>(a, bf16, store, blocks, st);

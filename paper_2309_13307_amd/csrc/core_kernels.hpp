@@ -145,6 +145,103 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
     }
 }
 
+// Matrix-pipe variant of the projection, used for passes of more than 8 clients (and selectable
+// with the environment variable CORE_PROJECT_VARIANT=mfma|valu for A/B runs).  Same lane mapping and generator as
+// project_kernel; the 4*NC v_fmac per call are replaced by NC v_mfma_f32_4x4x1_16B_f32: block
+// b = lane/4 of the instruction computes the 4x4 outer product of (xi of vectors 4b..4b+3) and
+// (G of clients 4g..4g+3) at one coordinate.  Lane l supplies A = its own normal and
+// B = G[4g + l%4][coordinate]; it receives D[i] = sum for vector 4(l/4)+i and client 4g + l%4.
+// fp32 MFMA has the same peak as the vector FMA on this chip and its issue does not overlap the
+// generator's VALU work, so the gain is small: measured ~4 % at 16 clients, a loss at 8.
+typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
+
+template <int NG, bool BF16>
+__global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
+{
+    constexpr int NC = 4 * NG;
+    constexpr int kRow = kTile + 4;   // 16-byte skew: the 4 client rows a wave reads hit distinct banks
+    __shared__ __attribute__((aligned(16))) float tile[NC][kRow];
+
+    const uint32_t b = blockIdx.x;
+    const uint32_t xcd = b & 7u;
+    const uint32_t s = b >> 3;
+    const uint32_t chunk = (s / a.jtiles) * 8u + xcd;
+    const uint32_t jt = s % a.jtiles;
+    if (chunk >= a.nchunks) return;
+
+    const uint32_t t = threadIdx.x;
+    const uint32_t j = jt * kThreads + t;
+    const uint32_t csub = t & 3u;
+
+    const uint64_t tiles_total = (a.d + kTile - 1) / kTile;
+    const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk;
+    uint64_t tile_end = tile_begin + a.tiles_per_chunk;
+    if (tile_end > tiles_total) tile_end = tiles_total;
+
+    Generator<3, 4> gen;
+    gen.init(a.k0, a.k1, a.r0, a.r1);
+
+    mfma_f32x4 outer[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) outer[g] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
+
+    float pre[NC];
+    auto fetch = [&](uint64_t tl) {
+        const uint64_t i = tl * kTile + t;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            float v = 0.0f;
+            if (i < a.d && (uint32_t)c < a.nc) v = load_g<BF16>(a.G, (uint64_t)(a.c0 + c) * a.ld + i);
+            pre[c] = v;
+        }
+    };
+    if (tile_begin < tile_end) fetch(tile_begin);
+
+    for (uint64_t tl = tile_begin; tl < tile_end; ++tl) {
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < NC; ++c) tile[c][t] = pre[c];
+        __syncthreads();
+        if (tl + 1 < tile_end) fetch(tl + 1);
+
+        mfma_f32x4 acc[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
+#pragma unroll 2
+        for (int qq = 0; qq < kTile / 4; ++qq) {
+            float z0, z1, z2, z3;
+            gen.block(q0 + (uint32_t)qq, j, z0, z1, z2, z3);
+            float4 gv[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) gv[g] = *reinterpret_cast<const float4*>(&tile[4 * g + csub][4 * qq]);
+            // coordinate-major order: consecutive instructions update different accumulators
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z0, gv[g].x, acc[g], 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z1, gv[g].y, acc[g], 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z2, gv[g].z, acc[g], 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z3, gv[g].w, acc[g], 0, 0, 0);
+        }
+#pragma unroll
+        for (int g = 0; g < NG; ++g) outer[g] += acc[g];
+    }
+
+    const uint32_t jrow = jt * kThreads + (t & ~3u);   // first of the 4 vectors this lane reports
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const uint32_t c = 4 * g + csub;
+        if (c < a.nc) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (jrow + i < a.m)
+                    a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + jrow + i] = kXiScale * outer[g][i];
+        }
+    }
+}
+
 // Stage A of the cross-chunk sum: part2[sy][e] = sum over this slice's chunks of part[k][e],
 // e = c*m + j.  Block = 64 outputs x 4 interleaved sub-slices; fixed order, fp64.
 __global__ void __launch_bounds__(kThreads) reduce_chunks_kernel(const float* __restrict__ part,

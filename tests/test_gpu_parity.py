@@ -235,3 +235,20 @@ def test_materialised_xi_variant(d, m, n, bf16):
     assert torch.equal(gt, gt_from)
     # and it agrees with the regenerating path to fp32 rounding
     assert parity.rel_l2(gt.cpu().numpy(), gt3.cpu().numpy()) < 2e-6
+
+
+@pytest.mark.parametrize("d,m,n,bf16", [(1030, 70, 3, False), (5000, 300, 8, True), (9001, 260, 16, True),
+                                          (4100, 64, 21, False), (3000, 129, 11, True)])
+def test_mfma_projection_variant(d, m, n, bf16, monkeypatch):
+    """The matrix-pipe A/B variant of the projection meets the same bars as the default kernel."""
+    _say(f"mfma variant d={d} m={m} n={n} bf16={bf16}")
+    monkeypatch.setenv("CORE_PROJECT_VARIANT", "mfma")
+    rng = np.random.default_rng(3 * d + m + n)
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
+    if bf16:
+        G = G.to(torch.bfloat16)
+    P, pbar, gt = _run_and_check(23, 5, G, m, what=f"mfma d={d} m={m} n={n}")
+    monkeypatch.setenv("CORE_PROJECT_VARIANT", "valu")
+    P2, pbar2 = core.core_compress_batched(23, 5, G, m)
+    _sync()
+    assert parity.rel_l2(P.cpu().numpy(), P2.cpu().numpy()) < 2e-6
