@@ -114,6 +114,37 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
                float *pbar, float *gtilde,
                void *ws, size_t ws_bytes, core_stream stream);
 
+/* ---- reconstruction fused with the optimiser step -------------------------------------------
+ * Algorithm 2 ends each round with x^{k+1} = x^k - h_k * gtilde; CORE-AGD (appendix, heavy-ball
+ * form) takes the gradients at y^k = x^k + (1-beta)(x^k - x^{k-1}) and sets
+ * x^{k+1} = y^k - h * gtilde.  These entry points do that step in the epilogue of the
+ * reconstruction kernel, so gtilde need not be written and re-read:
+ *   x_new[i]  = y[i] - h * scale * sum_j pbar[j] xi_j[i]
+ *   y_next[i] = x_new[i] + one_minus_beta * (x_new[i] - x_cur[i])     (only if y_next != NULL)
+ *   y      [d] device fp32: the point the gradients were taken at (x^k for CORE-GD)
+ *   x_new  [d] device fp32 out; may be the same buffer as y (in-place step)
+ *   x_cur, y_next: both NULL (plain gradient step) or both non-NULL; x_cur is the iterate
+ *           x^k; y_next may be the same buffer as x_cur or y, but not x_new
+ *   gtilde [d] device fp32 out, or NULL when the estimate itself is not wanted; must not alias
+ *           the other buffers.
+ * Every element is read before the same thread writes it, which is what makes the stated
+ * aliasing safe. */
+int core_reconstruct_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m,
+                            const float *pbar, float scale, float h,
+                            const float *y, float *x_new,
+                            const float *x_cur, float one_minus_beta, float *y_next,
+                            float *gtilde, core_stream stream);
+
+/* core_compress_batched(P = NULL) followed by core_reconstruct_update(scale = 1/m): one whole
+ * iteration of Algorithm 2 (or of CORE-AGD) apart from the evaluation of the client gradients. */
+int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                      const void *G, core_dtype dt, uint64_t ld,
+                      float *pbar, float h,
+                      const float *y, float *x_new,
+                      const float *x_cur, float one_minus_beta, float *y_next,
+                      float *gtilde,
+                      void *ws, size_t ws_bytes, core_stream stream);
+
 /* ---- materialised-Xi comparison variant ---------------------------------------------------
  * The matrix Xi = [xi_1 ... xi_m]^T of the paper's privacy appendix (p = Xi a) is normally never
  * stored.  These entry points store it once, while projecting, and read it back to reconstruct,

@@ -52,3 +52,21 @@ def core_gd(A, b, lam, n, m, h, rounds, seed, x0=None, first_round=0):
         x = x - h * gtilde
         losses.append(ridge_loss(A, b, lam, x))
     return x, np.array(losses)
+
+
+def core_agd(A, b, lam, n, m, h, beta, rounds, seed, x0=None, first_round=0):
+    """CORE-AGD (appendix, heavy-ball form): y^k = x^k + (1-beta)(x^k - x^{k-1}), the machines
+    project grad f_i(y^k), and x^{k+1} = y^k - h * estimator.  x^{-1} = x^0.
+    Returns (x, losses[rounds+1])."""
+    d = A.shape[1]
+    x = np.zeros(d) if x0 is None else np.array(x0, dtype=np.float64)
+    x_prev = x.copy()
+    losses = [ridge_loss(A, b, lam, x)]
+    for k in range(rounds):
+        y = x + (1.0 - beta) * (x - x_prev)
+        G = client_gradients(A, b, lam, y, n)
+        _, _, gtilde = core_round(seed, first_round + k, G, m)
+        x_prev = x
+        x = y - h * gtilde
+        losses.append(ridge_loss(A, b, lam, x))
+    return x, np.array(losses)

@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     CoreError, alloc_workspace, core_compress, core_compress_batched, core_debug_philox,
     core_debug_xi, core_reconstruct, core_round, core_workspace_bytes, load_library, strerror,
     alloc_xi, core_compress_batched_store_xi, core_reconstruct_from_xi, core_round_materialized,
-    core_xi_bytes,
+    core_xi_bytes, core_reconstruct_update, core_round_update,
 )

@@ -27,7 +27,7 @@ EXPORTS = (
     "core_strerror", "core_last_hip_error", "core_workspace_bytes", "core_compress",
     "core_compress_batched", "core_reconstruct", "core_round", "core_debug_philox", "core_debug_xi",
     "core_xi_bytes", "core_compress_batched_store_xi", "core_reconstruct_from_xi",
-    "core_round_materialized",
+    "core_round_materialized", "core_reconstruct_update", "core_round_update",
 )
 
 
@@ -73,6 +73,11 @@ def load_library() -> ctypes.CDLL:
     L.core_reconstruct_from_xi.restype = i32
     L.core_round_materialized.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz, vp, sz, vp]
     L.core_round_materialized.restype = i32
+    L.core_reconstruct_update.argtypes = [u64, u64, u64, u32, vp, f32, f32, vp, vp, vp, f32, vp, vp, vp]
+    L.core_reconstruct_update.restype = i32
+    L.core_round_update.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, f32, vp, vp, vp, f32, vp, vp,
+                                    vp, sz, vp]
+    L.core_round_update.restype = i32
     L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     L.core_debug_philox.restype = i32
     L.core_debug_xi.argtypes = [u64, u64, u32, u64, u64, vp, vp]
@@ -195,6 +200,42 @@ def core_round(seed: int, rnd: int, G: torch.Tensor, m: int, d: int | None = Non
                                    _stream())
     _check(rc, "core_round")
     return pbar, gtilde
+
+
+def _ptr(t):
+    return t.data_ptr() if t is not None else None
+
+
+def core_reconstruct_update(seed: int, rnd: int, pbar: torch.Tensor, scale: float, h: float,
+                            y: torch.Tensor, x_new: torch.Tensor, x_cur: torch.Tensor | None = None,
+                            one_minus_beta: float = 0.0, y_next: torch.Tensor | None = None,
+                            gtilde: torch.Tensor | None = None) -> None:
+    """x_new = y - h * scale * sum_j pbar[j] xi_j; optionally y_next = x_new + (1-beta)(x_new - x_cur)."""
+    _require_cuda(pbar, y, x_new, x_cur, y_next, gtilde)
+    d, m = y.numel(), pbar.numel()
+    rc = load_library().core_reconstruct_update(seed, rnd, d, m, pbar.data_ptr(), scale, h, y.data_ptr(),
+                                                x_new.data_ptr(), _ptr(x_cur), one_minus_beta,
+                                                _ptr(y_next), _ptr(gtilde), _stream())
+    _check(rc, "core_reconstruct_update")
+
+
+def core_round_update(seed: int, rnd: int, G: torch.Tensor, m: int, h: float, y: torch.Tensor,
+                      x_new: torch.Tensor, pbar: torch.Tensor, ws: torch.Tensor,
+                      x_cur: torch.Tensor | None = None, one_minus_beta: float = 0.0,
+                      y_next: torch.Tensor | None = None, gtilde: torch.Tensor | None = None,
+                      d: int | None = None) -> None:
+    """One iteration of Algorithm 2 / CORE-AGD apart from the gradient evaluation."""
+    _require_cuda(G, y, x_new, pbar, ws, x_cur, y_next, gtilde)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    rc = load_library().core_round_update(seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld,
+                                          pbar.data_ptr(), h, y.data_ptr(), x_new.data_ptr(), _ptr(x_cur),
+                                          one_minus_beta, _ptr(y_next), _ptr(gtilde), ws.data_ptr(),
+                                          ws.numel(), _stream())
+    _check(rc, "core_round_update")
 
 
 def core_xi_bytes(d: int, m: int) -> int:

@@ -51,10 +51,29 @@ class RidgeCoreGD:
         r = self.A.double() @ x - self.b.double()
         return float(0.5 * (r @ r) + 0.5 * self.lam * (x @ x))
 
-    def round(self, k: int, h: float, G: torch.Tensor | None = None) -> torch.Tensor:
-        """One round of Algorithm 2 with round counter k; returns the client gradients it used."""
+    def round(self, k: int, h: float, G: torch.Tensor | None = None, fused: bool = True) -> torch.Tensor:
+        """One round of Algorithm 2 with round counter k; returns the client gradients it used.
+        fused: the step x <- x - h * gtilde runs in the epilogue of the reconstruction kernel."""
         if G is None:
             G = self.client_gradients()
-        binding.core_round(self.seed, k, G, self.m, pbar=self.pbar, gtilde=self.gtilde, ws=self.ws)
-        self.x -= h * self.gtilde
+        if fused:
+            binding.core_round_update(self.seed, k, G, self.m, h, self.x, self.x, self.pbar, self.ws,
+                                      gtilde=self.gtilde)
+        else:
+            binding.core_round(self.seed, k, G, self.m, pbar=self.pbar, gtilde=self.gtilde, ws=self.ws)
+            self.x -= h * self.gtilde
         return G
+
+    def agd_round(self, k: int, h: float, beta: float) -> None:
+        """One round of CORE-AGD (heavy-ball form).  State: self.x = x^k, self.y = y^k (the
+        extrapolated point; equal to x^0 before the first round).  The kernel epilogue writes
+        x^{k+1} = y^k - h * gtilde and y^{k+1} = x^{k+1} + (1-beta)(x^{k+1} - x^k)."""
+        if not hasattr(self, "y"):
+            self.y = self.x.clone()
+            self.x_next = torch.empty_like(self.x)
+        x_keep, self.x = self.x, self.y      # gradients are taken at y^k
+        G = self.client_gradients()
+        self.x = x_keep
+        binding.core_round_update(self.seed, k, G, self.m, h, self.y, self.x_next, self.pbar, self.ws,
+                                  x_cur=self.x, one_minus_beta=1.0 - beta, y_next=self.y)
+        self.x, self.x_next = self.x_next, self.x

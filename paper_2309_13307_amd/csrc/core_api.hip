@@ -176,19 +176,49 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     return CORE_OK;
 }
 
+struct UpdateArgs {
+    const float* y = nullptr;
+    float* x_new = nullptr;
+    const float* x_cur = nullptr;
+    float* y_next = nullptr;
+    float h = 0.0f, omb = 0.0f;
+};
+
 int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
-                        float scale, float* gtilde, hipStream_t st)
+                        float scale, float* gtilde, hipStream_t st, const UpdateArgs* up = nullptr)
 {
     ReconArgs a;
     a.pbar = pbar; a.gtilde = gtilde; a.d = d; a.m = m; a.scale = scale;
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
     a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
-    a.vec_store = aligned_to(gtilde, 16) ? 1 : 0;
+    bool vec = !gtilde || aligned_to(gtilde, 16);
+    a.y = nullptr; a.x_new = nullptr; a.x_cur = nullptr; a.y_next = nullptr; a.h = 0.0f; a.omb = 0.0f;
+    if (up) {
+        a.y = up->y; a.x_new = up->x_new; a.x_cur = up->x_cur; a.y_next = up->y_next;
+        a.h = up->h; a.omb = up->omb;
+        vec = vec && aligned_to(up->y, 16) && aligned_to(up->x_new, 16) &&
+              (!up->y_next || (aligned_to(up->y_next, 16) && aligned_to(up->x_cur, 16)));
+    }
+    a.vec_store = vec ? 1 : 0;
     const uint64_t nblk = ceil_div(d, 4);
     const uint32_t blocks = (uint32_t)ceil_div(nblk, (uint64_t)kThreads * kReconBlocks);
-    hipLaunchKernelGGL(reconstruct_kernel, dim3(blocks), dim3(kThreads), 0, st, a);
+    if (up) hipLaunchKernelGGL(reconstruct_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, a);
+    else    hipLaunchKernelGGL(reconstruct_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
+    return CORE_OK;
+}
+
+int validate_update(const float* y, const float* x_new, const float* x_cur, const float* y_next,
+                    const float* gtilde)
+{
+    if (!y || !x_new) return CORE_ERR_INVALID_ARGUMENT;
+    if ((x_cur == nullptr) != (y_next == nullptr)) return CORE_ERR_INVALID_ARGUMENT;
+    if (y_next && (y_next == x_new || y_next == gtilde)) return CORE_ERR_INVALID_ARGUMENT;
+    if (gtilde && (gtilde == x_new || gtilde == y || gtilde == x_cur)) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(y, 4) || !aligned_to(x_new, 4) || !aligned_to(x_cur, 4) || !aligned_to(y_next, 4) ||
+        !aligned_to(gtilde, 4))
+        return CORE_ERR_MISALIGNED;
     return CORE_OK;
 }
 
@@ -278,6 +308,37 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
     rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
     if (rc != CORE_OK) return rc;
     return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream);
+}
+
+int core_reconstruct_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
+                            float scale, float h, const float* y, float* x_new, const float* x_cur,
+                            float one_minus_beta, float* y_next, float* gtilde, core_stream stream)
+{
+    if (!pbar || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(pbar, 4)) return CORE_ERR_MISALIGNED;
+    int rc = validate_update(y, x_new, x_cur, y_next, gtilde);
+    if (rc != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    UpdateArgs up;
+    up.y = y; up.x_new = x_new; up.x_cur = x_cur; up.y_next = y_next; up.h = h; up.omb = one_minus_beta;
+    return enqueue_reconstruct(seed, round, d, m, pbar, scale, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n, const void* G,
+                      core_dtype dt, uint64_t ld, float* pbar, float h, const float* y, float* x_new,
+                      const float* x_cur, float one_minus_beta, float* y_next, float* gtilde,
+                      void* ws, size_t ws_bytes, core_stream stream)
+{
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = validate_update(y, x_new, x_cur, y_next, gtilde)) != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
+    if (rc != CORE_OK) return rc;
+    UpdateArgs up;
+    up.y = y; up.x_new = x_new; up.x_cur = x_cur; up.y_next = y_next; up.h = h; up.omb = one_minus_beta;
+    return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream, &up);
 }
 
 size_t core_xi_bytes(uint64_t d, uint32_t m) { return xi_bytes(d, m); }

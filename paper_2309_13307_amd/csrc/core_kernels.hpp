@@ -288,9 +288,21 @@ struct ReconArgs {
     uint32_t m;
     float scale;
     uint32_t k0, k1, r0, r1;
-    int vec_store;        // gtilde is 16-byte aligned
+    int vec_store;        // every output (and y, x_cur) is 16-byte aligned
+    // fused optimiser step (UPDATE variant only)
+    const float* y;       // [d] point the gradients were taken at
+    float* x_new;         // [d] y - h * gtilde
+    const float* x_cur;   // [d] current iterate, for the heavy-ball extrapolation (or null)
+    float* y_next;        // [d] x_new + omb * (x_new - x_cur) (or null)
+    float h;
+    float omb;            // 1 - beta
 };
 
+// UPDATE: the reconstruction feeds the optimiser step in its epilogue instead of (or as well as)
+// writing gtilde: x_new = y - h * gtilde (last line of the loop of Algorithm 2; with y = y^k it is
+// the update of CORE-AGD), and optionally the next heavy-ball point
+// y_next = x_new + (1 - beta)(x_new - x_cur) (first line of the loop of CORE-AGD).
+template <bool UPDATE>
 __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
 {
     __shared__ float pb[kPbarTile];
@@ -348,15 +360,48 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
         if (q >= nblk) continue;
         const uint64_t i = 4 * q;
         const float sc = a.scale * kXiScale;
-        const float v0 = sc * outer[r][0], v1 = sc * outer[r][1];
-        const float v2 = sc * outer[r][2], v3 = sc * outer[r][3];
-        if (a.vec_store && i + 4 <= a.d) {
-            *reinterpret_cast<float4*>(a.gtilde + i) = make_float4(v0, v1, v2, v3);
-        } else {
-            if (i + 0 < a.d) a.gtilde[i + 0] = v0;
-            if (i + 1 < a.d) a.gtilde[i + 1] = v1;
-            if (i + 2 < a.d) a.gtilde[i + 2] = v2;
-            if (i + 3 < a.d) a.gtilde[i + 3] = v3;
+        float v[4] = {sc * outer[r][0], sc * outer[r][1], sc * outer[r][2], sc * outer[r][3]};
+        const bool full = a.vec_store && i + 4 <= a.d;
+        if (a.gtilde) {
+            if (full) {
+                *reinterpret_cast<float4*>(a.gtilde + i) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) if (i + k < a.d) a.gtilde[i + k] = v[k];
+            }
+        }
+        if constexpr (UPDATE) {
+            float yv[4] = {0.f, 0.f, 0.f, 0.f}, xc[4] = {0.f, 0.f, 0.f, 0.f};
+            if (full) {
+                const float4 t4 = *reinterpret_cast<const float4*>(a.y + i);
+                yv[0] = t4.x; yv[1] = t4.y; yv[2] = t4.z; yv[3] = t4.w;
+                if (a.y_next) {
+                    const float4 c4 = *reinterpret_cast<const float4*>(a.x_cur + i);
+                    xc[0] = c4.x; xc[1] = c4.y; xc[2] = c4.z; xc[3] = c4.w;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) if (i + k < a.d) {
+                    yv[k] = a.y[i + k];
+                    if (a.y_next) xc[k] = a.x_cur[i + k];
+                }
+            }
+            float xn[4], yn[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                xn[k] = fmaf(-a.h, v[k], yv[k]);
+                yn[k] = fmaf(a.omb, xn[k] - xc[k], xn[k]);
+            }
+            if (full) {
+                *reinterpret_cast<float4*>(a.x_new + i) = make_float4(xn[0], xn[1], xn[2], xn[3]);
+                if (a.y_next) *reinterpret_cast<float4*>(a.y_next + i) = make_float4(yn[0], yn[1], yn[2], yn[3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) if (i + k < a.d) {
+                    a.x_new[i + k] = xn[k];
+                    if (a.y_next) a.y_next[i + k] = yn[k];
+                }
+            }
         }
     }
 }

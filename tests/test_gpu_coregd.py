@@ -73,3 +73,29 @@ def test_config2_core_gd_ridge():
     # the strong-convexity step); one trajectory, so allow slack on the exponent
     mu = float(s.min() ** 2 + pr.lam)
     assert gaps[-1] <= gaps[0] * (1.0 - mu * h) ** (0.5 * pr.rounds)
+
+
+    # the fused step and the separate torch update give the same iterates to fp32 rounding
+    run2 = coregd.RidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed)
+    for k in range(20):
+        run2.round(k, h, fused=False)
+    run3 = coregd.RidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed)
+    for k in range(20):
+        run3.round(k, h, fused=True)
+    torch.cuda.synchronize()
+    assert float((run2.x - run3.x).norm() / run2.x.norm()) < 1e-6
+
+    # CORE-AGD (heavy-ball form) with the update and the next extrapolated point written by the
+    # kernel epilogue, against the oracle's fp64 run
+    _say("config2 problem: 60 rounds of CORE-AGD")
+    beta = 0.2
+    h_agd = 0.5 * h
+    run4 = coregd.RidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed)
+    for k in range(60):
+        run4.agd_round(k, h_agd, beta)
+    torch.cuda.synchronize()
+    x_agd_ref, losses_agd = ocoregd.core_agd(A64, b64, pr.lam, pr.n, pr.m, h_agd, beta, 60, pr.seed)
+    x_agd = run4.x.double().cpu().numpy()
+    print("CORE-AGD gap after 60 rounds: GPU path", run4.loss() - fstar, "oracle", losses_agd[-1] - fstar)
+    assert np.linalg.norm(x_agd - x_agd_ref) <= 1e-3 * np.linalg.norm(x_agd_ref)
+    assert abs((run4.loss() - fstar) - (losses_agd[-1] - fstar)) <= 5e-3 * (losses_agd[-1] - fstar)

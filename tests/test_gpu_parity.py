@@ -252,3 +252,56 @@ def test_mfma_projection_variant(d, m, n, bf16, monkeypatch):
     P2, pbar2 = core.core_compress_batched(23, 5, G, m)
     _sync()
     assert parity.rel_l2(P.cpu().numpy(), P2.cpu().numpy()) < 2e-6
+
+
+@pytest.mark.parametrize("d,m", [(5, 3), (4096, 64), (10007, 130)])
+def test_fused_optimiser_step(d, m):
+    """x_new = y - h * gtilde and y_next = x_new + (1-beta)(x_new - x_cur) in the kernel epilogue
+    (last line of the loop of Algorithm 2; the two update lines of CORE-AGD)."""
+    _say(f"fused update d={d} m={m}")
+    rng = np.random.default_rng(d + m)
+    pbar = rng.standard_normal(m).astype(np.float32)
+    y = rng.standard_normal(d).astype(np.float32)
+    xc = rng.standard_normal(d).astype(np.float32)
+    h, omb, scale = 0.37, 0.8, 1.0 / m
+    gt_ref = oracle.reconstruct(8, 2, pbar, scale, 0, d)
+    xn_ref = y.astype(np.float64) - h * gt_ref
+    yn_ref = xn_ref + omb * (xn_ref - xc.astype(np.float64))
+    step = np.linalg.norm(h * gt_ref)
+
+    def close(got, ref):
+        return np.linalg.norm(got.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * step + 2e-7 * np.linalg.norm(ref)
+
+    pb = torch.from_numpy(pbar).to(DEV)
+    yd, xcd = torch.from_numpy(y).to(DEV), torch.from_numpy(xc).to(DEV)
+    # plain step, separate output, gtilde also written
+    xn = torch.empty(d, dtype=torch.float32, device=DEV)
+    gt = torch.empty(d, dtype=torch.float32, device=DEV)
+    core.core_reconstruct_update(8, 2, pb, scale, h, yd, xn, gtilde=gt)
+    _sync()
+    parity.check_gtilde(gt.cpu().numpy(), gt_ref, "fused gtilde")
+    assert close(xn, xn_ref)
+    assert torch.equal(yd, torch.from_numpy(y).to(DEV)), "y must not be modified"
+    # in place, no gtilde
+    y2 = yd.clone()
+    core.core_reconstruct_update(8, 2, pb, scale, h, y2, y2)
+    _sync()
+    assert torch.equal(y2, xn)
+    # heavy-ball: y_next written over x_cur, x_new over y; and from 4-byte-aligned views
+    buf = torch.zeros(3 * (d + 4) + 3, dtype=torch.float32, device=DEV)
+    y3 = buf[1:1 + d]; y3.copy_(yd)
+    c3 = buf[d + 6:2 * d + 6]; c3.copy_(xcd)
+    core.core_reconstruct_update(8, 2, pb, scale, h, y3, y3, x_cur=c3, one_minus_beta=omb, y_next=c3)
+    _sync()
+    assert close(y3, xn_ref) and close(c3, yn_ref)
+    # the same through aligned, distinct buffers
+    xn4 = torch.empty_like(yd); yn4 = torch.empty_like(yd)
+    core.core_reconstruct_update(8, 2, pb, scale, h, yd, xn4, x_cur=xcd, one_minus_beta=omb, y_next=yn4)
+    _sync()
+    assert torch.equal(xn4, xn) and close(yn4, yn_ref)
+    assert torch.equal(yn4, c3) and torch.equal(xn4, y3)
+    # bad combinations are refused
+    with pytest.raises(core.CoreError):
+        core.core_reconstruct_update(8, 2, pb, scale, h, yd, xn4, x_cur=xcd, one_minus_beta=omb, y_next=None)
+    with pytest.raises(core.CoreError):
+        core.core_reconstruct_update(8, 2, pb, scale, h, yd, xn4, x_cur=xcd, one_minus_beta=omb, y_next=xn4)

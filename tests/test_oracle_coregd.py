@@ -89,3 +89,39 @@ def test_core_gd_reaches_the_closed_form_solution():
     x, losses = coregd.core_gd(A, b, lam, n, m, h, 600, seed=5)
     assert losses[-1] - fstar < 1e-6 * (losses[0] - fstar)
     assert np.linalg.norm(x - xs) < 1e-2 * np.linalg.norm(xs)
+
+
+def test_core_agd_is_heavy_ball_with_the_estimated_gradient():
+    """With a large budget m the estimator is nearly the gradient, so CORE-AGD must track the
+    deterministic heavy-ball iteration it is built on, and reach the closed-form minimiser."""
+    A, b, lam, n = _problem(d=6, rows=12, lam=0.05, decay=0.5)
+    d = A.shape[1]
+    H = A.T @ A + lam * np.eye(d)
+    ev = np.linalg.eigvalsh(H)
+    h = 1.0 / ev[-1]
+    beta = np.sqrt(h * ev[0])
+    xs = coregd.ridge_solution(A, b, lam)
+    # deterministic heavy ball
+    x = np.zeros(d); xp = x.copy(); traj = []
+    for k in range(60):
+        y = x + (1 - beta) * (x - xp)
+        g = A.T @ (A @ y - b) + lam * y
+        xp = x; x = y - h * g; traj.append(x.copy())
+    m = 20000
+    xc, losses = coregd.core_agd(A, b, lam, n, m, h, beta, 60, seed=3)
+    assert np.linalg.norm(xc - traj[-1]) < 0.05 * np.linalg.norm(xs)
+    assert np.linalg.norm(xc - xs) < 0.05 * np.linalg.norm(xs)
+    assert losses[-1] < losses[0]
+    # one step from a given (x, x_prev) pair: x1 = y - h * gtilde with y the extrapolated point
+    from oracle import core_round
+    x0 = np.arange(1.0, d + 1.0)
+    G = coregd.client_gradients(A, b, lam, x0, n)   # x_prev = x0 on the first step, so y = x0
+    _, _, gt = core_round(11, 0, G, 8)
+    x1, _ = coregd.core_agd(A, b, lam, n, 8, 0.1, 0.3, 1, seed=11, x0=x0)
+    np.testing.assert_allclose(x1, x0 - 0.1 * gt, rtol=1e-14, atol=1e-14)
+    # second step uses y = x1 + (1-beta)(x1 - x0)
+    y1 = x1 + 0.7 * (x1 - x0)
+    G1 = coregd.client_gradients(A, b, lam, y1, n)
+    _, _, gt1 = core_round(11, 1, G1, 8)
+    x2, _ = coregd.core_agd(A, b, lam, n, 8, 0.1, 0.3, 2, seed=11, x0=x0)
+    np.testing.assert_allclose(x2, y1 - 0.1 * gt1, rtol=1e-13, atol=1e-13)
