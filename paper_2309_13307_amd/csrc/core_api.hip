@@ -26,12 +26,13 @@ struct Plan {
     uint32_t jtiles;
     uint32_t nchunks;
     uint32_t tiles_per_chunk;
-    uint32_t S;            // slices of the cross-chunk sum
-    size_t part_off, part2_off, total;
+    uint32_t Z;            // slices of the cross-chunk sum
+    size_t part_off, psum_off, total;
 };
 
-// Split d into chunks of whole 256-coordinate tiles so that (chunks x vector tiles) fills the
-// chip several times over; sizes depend only on (d, m, n).
+// Split d into chunks of whole 256-coordinate tiles so that (chunks x vector tiles) is about
+// 8192 equal blocks: four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens
+// out speed differences between CUs.  Sizes depend only on (d, m, n).
 bool make_plan(uint64_t d, uint32_t m, uint32_t n, Plan& p)
 {
     if (d == 0 || d > kMaxD || m == 0 || n == 0 || n > kMaxN) return false;
@@ -42,14 +43,14 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, Plan& p)
     if (want > tiles_total) want = tiles_total;
     p.tiles_per_chunk = (uint32_t)ceil_div(tiles_total, want);
     p.nchunks = (uint32_t)ceil_div(tiles_total, p.tiles_per_chunk);
-    uint32_t S = p.nchunks / 64u;
-    if (S < 1) S = 1;
-    if (S > 16) S = 16;
-    p.S = S;
+    uint32_t Z = p.nchunks / 128u;
+    if (Z < 1) Z = 1;
+    if (Z > 16) Z = 16;
+    p.Z = Z;
     const uint64_t E = (uint64_t)n * m;
     size_t off = 0;
-    p.part_off = off;   off = align_up(off + (size_t)p.nchunks * E * sizeof(float), 256);
-    p.part2_off = off;  off = align_up(off + (size_t)S * E * sizeof(double), 256);
+    p.part_off = off;  off = align_up(off + (size_t)p.nchunks * E * sizeof(float), 256);
+    p.psum_off = off;  off = align_up(off + (size_t)Z * E * sizeof(double), 256);
     p.total = off;
     return true;
 }
@@ -133,7 +134,7 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
 {
     char* base = (char*)ws;
     float* part = (float*)(base + plan.part_off);
-    double* part2 = (double*)(base + plan.part2_off);
+    double* psum = (double*)(base + plan.psum_off);
 
     ProjectArgs a;
     a.G = G; a.ld = ld; a.d = d; a.m = m; a.n = n;
@@ -164,13 +165,12 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         if (e != hipSuccess) return hip_fail(e);
     }
 
-    const uint64_t E = (uint64_t)n * m;
-    hipLaunchKernelGGL(reduce_chunks_kernel, dim3((uint32_t)ceil_div(E, 64), plan.S), dim3(kThreads), 0, st,
-                       part, E, plan.nchunks, plan.S, part2);
+    hipLaunchKernelGGL(reduce_chunks_kernel, dim3((uint32_t)ceil_div(m, 32), n, plan.Z), dim3(kThreads), 0, st,
+                       part, m, n, plan.nchunks, psum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
-    hipLaunchKernelGGL(reduce_clients_kernel, dim3((uint32_t)ceil_div(m, kThreads)), dim3(kThreads), 0, st,
-                       part2, m, n, plan.S, P, pbar);
+    hipLaunchKernelGGL(reduce_clients_kernel, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), 0, st,
+                       psum, m, n, plan.Z, P, pbar);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     return CORE_OK;

@@ -242,43 +242,74 @@ __global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
     }
 }
 
-// Stage A of the cross-chunk sum: part2[sy][e] = sum over this slice's chunks of part[k][e],
-// e = c*m + j.  Block = 64 outputs x 4 interleaved sub-slices; fixed order, fp64.
+// Cross-chunk sum (a4), stage A: psum[z][c][j] = sum over the chunks of slice z of part[k][c][j],
+// fp64, fixed order.  grid = (ceil(m/32), n, Z); block = 32 vectors x 8 interleaved sub-slices.
+// Chunk k belongs to slice k % Z and, inside it, to sub-slice (k / Z) % 8.
 __global__ void __launch_bounds__(kThreads) reduce_chunks_kernel(const float* __restrict__ part,
-                                                                 uint64_t E, uint32_t nchunks,
-                                                                 uint32_t S, double* __restrict__ part2)
+                                                                 uint32_t m, uint32_t n, uint32_t nchunks,
+                                                                 double* __restrict__ psum)
 {
-    __shared__ double sh[4][64];
-    const uint32_t el = threadIdx.x & 63u;
-    const uint32_t sl = threadIdx.x >> 6;
-    const uint64_t e = (uint64_t)blockIdx.x * 64u + el;
-    const uint32_t sy = blockIdx.y;
+    __shared__ double sh[8][32];
+    const uint32_t jl = threadIdx.x & 31u;
+    const uint32_t sl = threadIdx.x >> 5;
+    const uint32_t j = blockIdx.x * 32u + jl;
+    const uint32_t c = blockIdx.y;
+    const uint32_t z = blockIdx.z, Z = gridDim.z;
+    const uint64_t E = (uint64_t)n * m;
     double s = 0.0;
-    if (e < E) {
-        for (uint32_t k = sy * 4u + sl; k < nchunks; k += 4u * S) s += (double)part[(uint64_t)k * E + e];
+    if (j < m) {
+        const float* src = part + (uint64_t)c * m + j;
+        const uint64_t step = 8ull * Z;
+        uint64_t k = (uint64_t)sl * Z + z;
+        // four independent loads in flight per thread; each sub-slice still adds in increasing k
+        for (; k + 3 * step < nchunks; k += 4 * step) {
+            const float v0 = src[k * E], v1 = src[(k + step) * E];
+            const float v2 = src[(k + 2 * step) * E], v3 = src[(k + 3 * step) * E];
+            s += (double)v0; s += (double)v1; s += (double)v2; s += (double)v3;
+        }
+        for (; k < nchunks; k += step) s += (double)src[k * E];
     }
-    sh[sl][el] = s;
+    sh[sl][jl] = s;
     __syncthreads();
-    if (sl == 0 && e < E) part2[(uint64_t)sy * E + e] = ((sh[0][el] + sh[1][el]) + sh[2][el]) + sh[3][el];
+    if (sl == 0 && j < m) {
+        double tot = sh[0][jl];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) tot += sh[q][jl];
+        psum[((uint64_t)z * n + c) * m + j] = tot;
+    }
 }
 
-// Stage B: P[c][j] = sum_sy part2[sy][c*m+j];  pbar[j] = (1/n) sum_c P[c][j].
-__global__ void __launch_bounds__(kThreads) reduce_clients_kernel(const double* __restrict__ part2,
-                                                                  uint32_t m, uint32_t n, uint32_t S,
+// Stage B: P[c][j] = sum_z psum[z][c][j]; the client mean of Eq. (tildefdef),
+// pbar[j] = (1/n) sum_c P[c][j].  Block = 32 vectors x 8 client lanes (lane cl takes clients
+// cl, cl+8, ...); fp64, fixed order.
+__global__ void __launch_bounds__(kThreads) reduce_clients_kernel(const double* __restrict__ psum,
+                                                                  uint32_t m, uint32_t n, uint32_t Z,
                                                                   float* __restrict__ P,
                                                                   float* __restrict__ pbar)
 {
-    const uint32_t j = blockIdx.x * kThreads + threadIdx.x;
-    if (j >= m) return;
+    __shared__ double sh[8][32];
+    const uint32_t jl = threadIdx.x & 31u;
+    const uint32_t cl = threadIdx.x >> 5;
+    const uint32_t j = blockIdx.x * 32u + jl;
     const uint64_t E = (uint64_t)n * m;
     double tot = 0.0;
-    for (uint32_t c = 0; c < n; ++c) {
-        double s = 0.0;
-        for (uint32_t sy = 0; sy < S; ++sy) s += part2[(uint64_t)sy * E + (uint64_t)c * m + j];
-        if (P) P[(uint64_t)c * m + j] = (float)s;
-        tot += s;
+    if (j < m) {
+        for (uint32_t c = cl; c < n; c += 8) {
+            const double* src = psum + (uint64_t)c * m + j;
+            double s = 0.0;
+            for (uint32_t z = 0; z < Z; ++z) s += src[(uint64_t)z * E];
+            if (P) P[(uint64_t)c * m + j] = (float)s;
+            tot += s;
+        }
     }
-    pbar[j] = (float)(tot / (double)n);
+    sh[cl][jl] = tot;
+    __syncthreads();
+    if (cl == 0 && j < m) {
+        double t = sh[0][jl];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) t += sh[q][jl];
+        pbar[j] = (float)(t / (double)n);
+    }
 }
 
 struct ReconArgs {
@@ -339,12 +370,15 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
 #pragma unroll
                 for (int r = 0; r < kReconBlocks; ++r) {
                     const uint32_t q = (uint32_t)(qbase + (uint64_t)r * kThreads);
-                    float z0, z1, z2, z3;
-                    gen.block(q, j, z0, z1, z2, z3);
-                    acc[r][0] = fmaf(p, z0, acc[r][0]);
-                    acc[r][1] = fmaf(p, z1, acc[r][1]);
-                    acc[r][2] = fmaf(p, z2, acc[r][2]);
-                    acc[r][3] = fmaf(p, z3, acc[r][3]);
+                    const Words w = gen.words(q, j);
+                    float ra, ca, sa, rb, cb, sb;
+                    gen.polar(w.x0, w.x1, ra, ca, sa);
+                    gen.polar(w.x2, w.x3, rb, cb, sb);
+                    const float pa = p * ra, pb2 = p * rb;   // pbar[j] folded into the radius
+                    acc[r][0] = fmaf(pa, ca, acc[r][0]);
+                    acc[r][1] = fmaf(pa, sa, acc[r][1]);
+                    acc[r][2] = fmaf(pb2, cb, acc[r][2]);
+                    acc[r][3] = fmaf(pb2, sb, acc[r][3]);
                 }
             }
 #pragma unroll

@@ -94,6 +94,18 @@ struct Generator {
         z_odd  = r * __builtin_amdgcn_sinf(u2);
     }
 
+    // Polar form of the same two normals: radius / kXiScale, cosine, sine.  A consumer that
+    // multiplies every normal by one factor p can fold p into the radius (one multiply per pair
+    // instead of two).
+    __device__ __forceinline__ void polar(uint32_t xa, uint32_t xb, float& r, float& c, float& s) const
+    {
+        const float u1 = fmaf((float)(xa >> 8), two_m24, two_m24);
+        const float u2 = (float)(xb >> 8) * 0x1p-24f;
+        r = __builtin_amdgcn_sqrtf(-__builtin_amdgcn_logf(u1));
+        c = __builtin_amdgcn_cosf(u2);
+        s = __builtin_amdgcn_sinf(u2);
+    }
+
     // xi_j[4q .. 4q+3] / kXiScale
     __device__ __forceinline__ void block(uint32_t q, uint32_t j, float& z0, float& z1, float& z2, float& z3) const
     {
