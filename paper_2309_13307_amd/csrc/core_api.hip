@@ -22,6 +22,8 @@ constexpr uint32_t kTargetBlocks = 8192;      // projection blocks wanted: 4 per
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr uint32_t kBlockSlots = 2048;   // resident 256-thread blocks: 256 CUs x 8
+
 struct Plan {
     uint32_t jtiles;
     uint32_t nchunks;
@@ -201,9 +203,18 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     }
     a.vec_store = vec ? 1 : 0;
     const uint64_t nblk = ceil_div(d, 4);
-    const uint32_t blocks = (uint32_t)ceil_div(nblk, (uint64_t)kThreads * kReconBlocks);
-    if (up) hipLaunchKernelGGL(reconstruct_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, a);
-    else    hipLaunchKernelGGL(reconstruct_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, a);
+    // two Philox blocks per thread share the scalar work of a vector; one per thread when that
+    // would leave block slots empty (small d)
+    const bool two = ceil_div(nblk, (uint64_t)kThreads * 2) >= 2 * kBlockSlots;
+    const uint32_t blocks = (uint32_t)ceil_div(nblk, (uint64_t)kThreads * (two ? 2 : 1));
+    const dim3 g(blocks), b(kThreads);
+    if (up) {
+        if (two) hipLaunchKernelGGL((reconstruct_kernel<true, 2>), g, b, 0, st, a);
+        else     hipLaunchKernelGGL((reconstruct_kernel<true, 1>), g, b, 0, st, a);
+    } else {
+        if (two) hipLaunchKernelGGL((reconstruct_kernel<false, 2>), g, b, 0, st, a);
+        else     hipLaunchKernelGGL((reconstruct_kernel<false, 1>), g, b, 0, st, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     return CORE_OK;

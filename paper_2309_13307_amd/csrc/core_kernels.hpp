@@ -26,7 +26,6 @@ namespace core {
 
 constexpr int kThreads = 256;     // threads per block in every kernel
 constexpr int kTile = 256;        // coordinates of G staged in LDS per step (64 Philox blocks)
-constexpr int kReconBlocks = 2;   // Philox blocks per thread in the reconstruction kernel
 constexpr int kPbarTile = 1024;   // pbar values staged in LDS per step
 
 struct ProjectArgs {
@@ -333,7 +332,7 @@ struct ReconArgs {
 // writing gtilde: x_new = y - h * gtilde (last line of the loop of Algorithm 2; with y = y^k it is
 // the update of CORE-AGD), and optionally the next heavy-ball point
 // y_next = x_new + (1 - beta)(x_new - x_cur) (first line of the loop of CORE-AGD).
-template <bool UPDATE>
+template <bool UPDATE, int kReconBlocks>
 __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
 {
     __shared__ float pb[kPbarTile];
