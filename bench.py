@@ -160,6 +160,12 @@ def main():
     esize = 2 if G.dtype == torch.bfloat16 else 4
     algo_bytes = float(n) * d * esize + 4.0 * d
 
+    # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled
+    # by what the same counters read for a 1 GiB copy: x2.000 and x1.000).  Counters cannot be read
+    # from inside this process, so the figure is the one measured for the default workload and is
+    # reported for that workload only: 410.9 MB fetched (G, once) + 66.8 MB written (partials).
+    traffic = 477.6e6 if (args.workload == "config4" and not mat) else None
+
     out = {
         "metric": "projected coords/sec (d*m*n/s) for compress+reconstruct",
         "value": value,
@@ -186,7 +192,7 @@ def main():
             "peak": PEAK_LANE_OPS / 1e12,
             "unit": "Tlaneop/s",
             "frac": ach_proj / PEAK_LANE_OPS,
-            "traffic": None,
+            "traffic": traffic,
             "ms": t_proj * 1e3,
             "lane_ops_per_pair": OPS_GENERATE + n,
             "second_kernel": {
