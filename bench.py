@@ -121,13 +121,18 @@ def main():
         rnd += 1
     torch.cuda.synchronize()
 
-    # timed region: exactly K rounds with distinct round counters
+    # timed region: exactly K rounds with distinct round counters; an event between rounds gives
+    # the per-round spread (events are recorded on the stream the kernels are launched on)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for k in range(args.steps):
         one_round(rnd)
+        marks[k + 1].record()
         rnd += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_round = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
     ms_per_step = elapsed * 1e3 / args.steps
     units = float(d) * m * n
     value = units / (elapsed / args.steps)
@@ -184,6 +189,8 @@ def main():
                         f"{'bf16' if esize == 2 else 'fp32'}, fp32 arithmetic, inputs resident in HBM",
             "d": d, "m": m, "n": n, "variant": args.variant,
         },
+        "ms_per_step_median": per_round[len(per_round) // 2],
+        "ms_per_step_min": per_round[0],
         "pct_fp32_valu_peak": 100.0 * ach_round / PEAK_LANE_OPS,
         "roofline": {
             "bound": "alu",
