@@ -74,6 +74,7 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
 
     const uint32_t t = threadIdx.x;
     const uint32_t j = jt * kThreads + t;
+    const bool wave_active = (jt * kThreads + (t & ~63u)) < a.m;   // wave-uniform
 
     const uint64_t tiles_total = (a.d + kTile - 1) / kTile;
     const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk;
@@ -112,6 +113,7 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
         const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
+        if (!wave_active) continue;   // this wave only helps staging G (m is not a multiple of 256)
 #pragma unroll 2
         for (int qq = 0; qq < kTile / 4; ++qq) {
             float z0, z1, z2, z3;

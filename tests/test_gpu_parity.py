@@ -71,7 +71,7 @@ def test_xi_close_to_oracle(seed, rnd, j, i0, count):
 def _run_and_check(seed, rnd, G_dev, m, d=None, what=""):
     n = G_dev.shape[0]
     d = G_dev.shape[1] if d is None else d
-    G_host = workloads.to_host(G_dev)[:, :d]
+    G_host = workloads.to_host(G_dev[:, :d])
     P_ref, pbar_ref, gt_ref = oracle.core_round(seed, rnd, np.ascontiguousarray(G_host), m)
     norms = parity.row_norms(G_host)
 
@@ -305,3 +305,27 @@ def test_fused_optimiser_step(d, m):
         core.core_reconstruct_update(8, 2, pb, scale, h, yd, xn4, x_cur=xcd, one_minus_beta=omb, y_next=None)
     with pytest.raises(core.CoreError):
         core.core_reconstruct_update(8, 2, pb, scale, h, yd, xn4, x_cur=xcd, one_minus_beta=omb, y_next=xn4)
+
+
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        d = int(rng.choice([rng.integers(1, 40), rng.integers(40, 3000), rng.integers(3000, 40000)]))
+        m = int(rng.choice([rng.integers(1, 20), rng.integers(20, 300), rng.integers(300, 800)]))
+        n = int(rng.choice([rng.integers(1, 9), rng.integers(9, 17), rng.integers(17, 40)]))
+        out.append((d, m, n, bool(rng.integers(0, 2)), int(rng.integers(0, 6))))
+    return out
+
+
+@pytest.mark.parametrize("d,m,n,bf16,pad", _random_shapes(24, 2024))
+def test_random_shapes(d, m, n, bf16, pad):
+    """Seeded random shapes, both input types, padded rows: every kernel template and tail."""
+    _say(f"random shape d={d} m={m} n={n} bf16={bf16} pad={pad}")
+    rng = np.random.default_rng(d * 131 + m * 17 + n)
+    full = torch.from_numpy((rng.standard_normal((n, d + pad)) * rng.uniform(1e-3, 10.0)).astype(np.float32)).to(DEV)
+    if bf16:
+        full = full.to(torch.bfloat16)
+    G = full[:, :d] if pad else full
+    assert G.stride(0) == d + pad
+    _run_and_check(1000 + d, m * n, G, m, d=d, what=f"random d={d} m={m} n={n}")
