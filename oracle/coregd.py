@@ -70,3 +70,40 @@ def core_agd(A, b, lam, n, m, h, beta, rounds, seed, x0=None, first_round=0):
         x = y - h * gtilde
         losses.append(ridge_loss(A, b, lam, x))
     return x, np.array(losses)
+
+
+def ring_gossip_matrix(n):
+    """Symmetric doubly-stochastic gossip matrix of a ring: 1/2 on the diagonal, 1/4 to each neighbour."""
+    W = np.zeros((n, n))
+    for i in range(n):
+        W[i, i] += 0.5
+        W[i, (i + 1) % n] += 0.25
+        W[i, (i - 1) % n] += 0.25
+    return W
+
+
+def decentralized_core_gd(A, b, lam, n, m, h, rounds, seed, W, gossip_steps, x0=None):
+    """Decentralized CORE-GD (appendix): machine i projects its own gradient, the machines average
+    the m-vectors p_i by `gossip_steps` multiplications with the gossip matrix W (the exact
+    solution of the m-dimensional subproblem is the mean), and machine i reconstructs with the
+    factor n/m from its own averaged vector and steps its own copy x_i.  Following Eq.
+    (tildefdef) for the scale of the objective (f is the mean of the f_i), the step uses the
+    reconstruction divided by n.  Returns (X [n, d], losses of the mean iterate)."""
+    from . import compress, reconstruct
+    d = A.shape[1]
+    rows = A.shape[0] // n
+    X = np.zeros((n, d)) if x0 is None else np.tile(np.asarray(x0, dtype=np.float64), (n, 1))
+    losses = [ridge_loss(A, b, lam, X.mean(axis=0))]
+    for k in range(rounds):
+        G = np.empty((n, d))
+        for c in range(n):
+            Ac, bc = A[c * rows:(c + 1) * rows], b[c * rows:(c + 1) * rows]
+            G[c] = n * (Ac.T @ (Ac @ X[c] - bc)) + lam * X[c]
+        P = compress(seed, k, G, m)                 # [n, m]: machine i's own projections
+        for _ in range(gossip_steps):
+            P = W @ P
+        for c in range(n):
+            gt_sum = reconstruct(seed, k, P[c], n / m, 0, d)   # (n/m) sum_j p_j xi_j
+            X[c] = X[c] - h * gt_sum / n
+        losses.append(ridge_loss(A, b, lam, X.mean(axis=0)))
+    return X, np.array(losses)

@@ -77,3 +77,37 @@ class RidgeCoreGD:
         binding.core_round_update(self.seed, k, G, self.m, h, self.y, self.x_next, self.pbar, self.ws,
                                   x_cur=self.x, one_minus_beta=1.0 - beta, y_next=self.y)
         self.x, self.x_next = self.x_next, self.x
+
+
+class DecentralizedRidgeCoreGD:
+    """Decentralized CORE-GD (appendix of the paper) with the n machines batched on one GPU.
+
+    Machine c keeps its own iterate X[c].  Per round: every machine projects its own gradient
+    (`core_compress_batched` with P requested), the m-vectors are averaged by a few
+    multiplications with the gossip matrix W (torch; on real hardware this is the only exchange),
+    and machine c reconstructs from its own averaged vector with the factor n/m and takes its step
+    in the kernel epilogue (`core_reconstruct_update`).  As in Eq. (tildefdef) the objective is the
+    mean of the f_c, so the step is h/n times the n/m-scaled reconstruction."""
+
+    def __init__(self, A: np.ndarray, b: np.ndarray, lam: float, n: int, m: int, seed: int,
+                 W: np.ndarray, gossip_steps: int, device="cuda"):
+        rows, d = A.shape
+        assert rows % n == 0
+        self.A3 = torch.from_numpy(np.ascontiguousarray(A, dtype=np.float32)).to(device).view(n, rows // n, d)
+        self.b3 = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(device).view(n, rows // n, 1)
+        self.W = torch.from_numpy(np.ascontiguousarray(W, dtype=np.float32)).to(device)
+        self.lam, self.n, self.m, self.seed, self.d = lam, n, m, seed, d
+        self.gossip_steps = gossip_steps
+        self.X = torch.zeros((n, d), dtype=torch.float32, device=device)
+        self.ws = binding.alloc_workspace(d, m, n, device)
+
+    def round(self, k: int, h: float) -> None:
+        r3 = torch.bmm(self.A3, self.X.unsqueeze(-1)) - self.b3                  # [n, rows/n, 1]
+        G = (self.n * torch.bmm(self.A3.transpose(1, 2), r3).squeeze(-1) + self.lam * self.X).contiguous()
+        P, _ = binding.core_compress_batched(self.seed, k, G, self.m, ws=self.ws)
+        for _ in range(self.gossip_steps):
+            P = self.W @ P
+        P = P.contiguous()
+        for c in range(self.n):
+            binding.core_reconstruct_update(self.seed, k, P[c], self.n / self.m, h / self.n,
+                                            self.X[c], self.X[c])

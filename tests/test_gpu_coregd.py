@@ -99,3 +99,25 @@ def test_config2_core_gd_ridge():
     print("CORE-AGD gap after 60 rounds: GPU path", run4.loss() - fstar, "oracle", losses_agd[-1] - fstar)
     assert np.linalg.norm(x_agd - x_agd_ref) <= 1e-3 * np.linalg.norm(x_agd_ref)
     assert abs((run4.loss() - fstar) - (losses_agd[-1] - fstar)) <= 5e-3 * (losses_agd[-1] - fstar)
+
+
+def test_decentralized_core_gd_small():
+    """Decentralized CORE-GD: per-machine projections, gossip averaging, reconstruction with n/m
+    and the step in the kernel epilogue, against the oracle's fp64 run."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    _say("decentralized CORE-GD d=512 m=32 n=8, 12 rounds, 3 gossip steps on a ring")
+    pr = workloads.ridge_problem(rows=1024, d=512, n=8, m=32, lam=1e-2, rounds=12)
+    s = 1.0 / np.arange(1, 513)
+    h = coregd.step_size(s, pr.lam, pr.m)
+    W = ocoregd.ring_gossip_matrix(pr.n)
+    run = coregd.DecentralizedRidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed, W, 3)
+    for k in range(pr.rounds):
+        run.round(k, h)
+    torch.cuda.synchronize()
+    X_ref, losses = ocoregd.decentralized_core_gd(pr.A.astype(np.float64), pr.b.astype(np.float64), pr.lam,
+                                                   pr.n, pr.m, h, pr.rounds, pr.seed, W, 3)
+    X = run.X.double().cpu().numpy()
+    assert np.linalg.norm(X - X_ref) <= 1e-4 * np.linalg.norm(X_ref)
+    assert np.abs(X_ref - X_ref.mean(axis=0)).max() > 1e-6     # the copies really differ
+    assert losses[-1] < losses[0]

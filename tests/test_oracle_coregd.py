@@ -125,3 +125,25 @@ def test_core_agd_is_heavy_ball_with_the_estimated_gradient():
     _, _, gt1 = core_round(11, 1, G1, 8)
     x2, _ = coregd.core_agd(A, b, lam, n, 8, 0.1, 0.3, 2, seed=11, x0=x0)
     np.testing.assert_allclose(x2, y1 - 0.1 * gt1, rtol=1e-13, atol=1e-13)
+
+
+def test_decentralized_core_gd_reduces_to_the_centralized_one():
+    """With enough gossip steps every machine holds the exact mean of the projections, and the
+    decentralized iteration (reconstruction with n/m on the mean) is CORE-GD itself."""
+    A, b, lam, n = _problem(d=8, rows=16, lam=0.1)
+    d = A.shape[1]
+    ev = np.linalg.eigvalsh(A.T @ A + lam * np.eye(d))
+    m = 4
+    h = m / (3.0 * ev.sum() + 2.0 * m * ev[-1])
+    W = coregd.ring_gossip_matrix(n)
+    np.testing.assert_allclose(W.sum(axis=0), 1.0)
+    np.testing.assert_allclose(W, W.T)
+    x_c, losses_c = coregd.core_gd(A, b, lam, n, m, h, 30, seed=9)
+    X, losses_d = coregd.decentralized_core_gd(A, b, lam, n, m, h, 30, 9, W, gossip_steps=200)
+    for c in range(n):
+        np.testing.assert_allclose(X[c], x_c, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(losses_d, losses_c, rtol=1e-9, atol=1e-12)
+    # with few gossip steps the copies differ but still make progress
+    X2, losses2 = coregd.decentralized_core_gd(A, b, lam, n, m, h, 30, 9, W, gossip_steps=2)
+    assert np.abs(X2 - X2.mean(axis=0)).max() > 1e-6
+    assert losses2[-1] < losses2[0]
