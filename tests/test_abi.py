@@ -128,3 +128,22 @@ def test_materialised_variant_arguments():
     h = L.core_compress_batched_store_xi
     assert h(1, 0, 1024, 16, 4, FAKE, 0, 1024, None, FAKE, FAKE, xb, FAKE, wsb - 1, None) == E.ERR_WORKSPACE_TOO_SMALL
     assert h(1, 0, 1024, 16, 4, FAKE, 0, 1024, None, FAKE, None, xb, FAKE, wsb, None) == E.ERR_INVALID_ARGUMENT
+
+
+def test_header_compiles_and_links_from_plain_c(tmp_path):
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    core.load_library()
+    from paper_2309_13307_amd import build as hip_build
+    libdir = os.path.dirname(hip_build.LIB_PATH)
+    exe = str(tmp_path / "abi_c_client")
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                    "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "native", "abi_c_client.c"),
+                    "-o", exe, "-L", libdir, "-l:libcore_hip.so", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    assert "c client ok" in res.stdout

@@ -134,7 +134,7 @@ def test_box_muller_special_values():
 
 def test_normals_have_gaussian_moments_and_law():
     """E z = 0, E z^2 = 1, E z^4 = 3 (the two moments the proof of Lemma 3.2 uses), KS vs N(0,1)."""
-    N = 4_000_000
+    N = 10_000_000
     z = oracle.xi_range(3, 0, 5, 0, N)
     s = 1.0 / np.sqrt(N)
     assert abs(z.mean()) < 5 * s
