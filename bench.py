@@ -44,7 +44,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config4", choices=["config3", "config4", "config5"])
+    ap.add_argument("--workload", default="config4", choices=["config1", "config2", "config3", "config4", "config5"],
+                    help="config4 is the headline; config1/config2 are single rounds of those small shapes "
+                         "(launch-bound), config2's full CORE-GD run lives in the tests")
     ap.add_argument("--variant", default="regenerate", choices=["regenerate", "materialized"],
                     help="materialized = the comparison variant that stores Xi while projecting and "
                          "reads it back to reconstruct (needs 4*d*m bytes of HBM)")
@@ -98,8 +100,8 @@ def main():
         return 0
     core.load_library()
 
-    case = {"config3": workloads.config3, "config4": workloads.config4,
-            "config5": workloads.config5}[args.workload](dev)
+    case = {"config1": workloads.config1, "config2": workloads.config2_round, "config3": workloads.config3,
+            "config4": workloads.config4, "config5": workloads.config5}[args.workload](dev)
     d, m, n = case.d, case.m, case.n
     G = case.G
     ws = core.alloc_workspace(d, m, n, dev)

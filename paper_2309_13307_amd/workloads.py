@@ -35,6 +35,17 @@ def config1(device="cpu") -> RoundCase:
     return RoundCase("config1", 1024, 16, 4, 42, (0,), torch.from_numpy(G).to(device))
 
 
+def config2_round(device="cpu") -> RoundCase:
+    """One round of config 2's shape (d=4096, m=64, n=8, fp32) on gradient-like inputs: a common
+    direction plus per-client noise.  The full CORE-GD run of config 2 is `ridge_problem`."""
+    d, n = 4096, 8
+    common = np.random.default_rng(20).standard_normal(d) / np.arange(1, d + 1) ** 0.5
+    G = np.empty((n, d), dtype=np.float32)
+    for c in range(n):
+        G[c] = (common + 0.3 * np.random.default_rng(21 + c).standard_normal(d)).astype(np.float32)
+    return RoundCase("config2", d, 64, n, 2, (0,), torch.from_numpy(G).to(device))
+
+
 def config3(device="cpu") -> RoundCase:
     d, n = 1 << 20, 8
     common = np.random.default_rng(0).standard_normal(d)
