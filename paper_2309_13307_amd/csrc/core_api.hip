@@ -25,26 +25,46 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr uint32_t kBlockSlots = 2048;   // resident 256-thread blocks: 256 CUs x 8
 
 struct Plan {
-    uint32_t jtiles;
+    bool qmode;            // lanes-over-q projection (few vectors or little work)
+    uint32_t jtiles;       // vector tiles (256 vectors) or, in qmode, groups of kQJ vectors
     uint32_t nchunks;
     uint32_t tiles_per_chunk;
     uint32_t Z;            // slices of the cross-chunk sum
     size_t part_off, psum_off, total;
 };
 
-// Split d into chunks of whole 256-coordinate tiles so that (chunks x vector tiles) is about
-// 8192 equal blocks: four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens
-// out speed differences between CUs.  Sizes depend only on (d, m, n).
-bool make_plan(uint64_t d, uint32_t m, uint32_t n, Plan& p)
+constexpr uint32_t kQTilesPerChunkMax = 64;   // bounds the fp32 chains of the lanes-over-q kernel
+
+// Split d into chunks of whole tiles so that (chunks x vector tiles) is about 8192 equal blocks:
+// four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens out speed differences
+// between CUs.  With fewer than 64 vectors, or too little work to fill the chip that way, the
+// lanes-over-q projection is planned instead.  Sizes depend only on (d, m, n).
+bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
 {
     if (d == 0 || d > kMaxD || m == 0 || n == 0 || n > kMaxN) return false;
     const uint64_t tiles_total = ceil_div(d, kTile);
-    p.jtiles = (uint32_t)ceil_div(m, kThreads);
-    uint64_t want = ceil_div(kTargetBlocks, p.jtiles);
-    if (want < 1) want = 1;
-    if (want > tiles_total) want = tiles_total;
-    p.tiles_per_chunk = (uint32_t)ceil_div(tiles_total, want);
-    p.nchunks = (uint32_t)ceil_div(tiles_total, p.tiles_per_chunk);
+    const char* forced = getenv("CORE_PROJECT_VARIANT");   // A/B switch: valu | mfma | q
+    if (forced && strcmp(forced, "q") == 0) p.qmode = allow_qmode;
+    else if (forced && (strcmp(forced, "valu") == 0 || strcmp(forced, "mfma") == 0)) p.qmode = false;
+    else p.qmode = allow_qmode && (m < 64 || ceil_div(m, 64) * tiles_total <= 1024);
+    if (p.qmode) {
+        const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
+        p.jtiles = (uint32_t)ceil_div(m, kQJ);
+        uint64_t want = ceil_div(kTargetBlocks / 2, p.jtiles);
+        if (want < 1) want = 1;
+        if (want > qtiles) want = qtiles;
+        uint64_t tpc = ceil_div(qtiles, want);
+        if (tpc > kQTilesPerChunkMax) tpc = kQTilesPerChunkMax;
+        p.tiles_per_chunk = (uint32_t)tpc;
+        p.nchunks = (uint32_t)ceil_div(qtiles, tpc);
+    } else {
+        p.jtiles = (uint32_t)ceil_div(m, kThreads);
+        uint64_t want = ceil_div(kTargetBlocks, p.jtiles);
+        if (want < 1) want = 1;
+        if (want > tiles_total) want = tiles_total;
+        p.tiles_per_chunk = (uint32_t)ceil_div(tiles_total, want);
+        p.nchunks = (uint32_t)ceil_div(tiles_total, p.tiles_per_chunk);
+    }
     uint32_t Z = p.nchunks / 128u;
     if (Z < 1) Z = 1;
     if (Z > 16) Z = 16;
@@ -55,6 +75,14 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, Plan& p)
     p.psum_off = off;  off = align_up(off + (size_t)Z * E * sizeof(double), 256);
     p.total = off;
     return true;
+}
+
+// Workspace that serves every entry point for these sizes (either projection plan).
+size_t workspace_bytes(uint64_t d, uint32_t m, uint32_t n)
+{
+    Plan a, b;
+    if (!make_plan(d, m, n, true, a) || !make_plan(d, m, n, false, b)) return 0;
+    return a.total > b.total ? a.total : b.total;
 }
 
 int hip_fail(hipError_t e)
@@ -98,9 +126,19 @@ hipError_t launch_project_mfma(const ProjectArgs& a, bool bf16, uint32_t blocks,
     return hipGetLastError();
 }
 
+template <int NC>
+hipError_t launch_project_q(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+{
+    const dim3 g(blocks), b(kThreads);
+    if (bf16) hipLaunchKernelGGL((project_q_kernel<NC, true>), g, b, 0, st, a);
+    else      hipLaunchKernelGGL((project_q_kernel<NC, false>), g, b, 0, st, a);
+    return hipGetLastError();
+}
+
 // Which projection kernel serves a pass of nc clients.  Measured on MI355X (config 5, n = 16):
 // the matrix-pipe kernel is ~4 % faster than the VALU kernel at 16 clients and ~5 % slower at 8,
-// so it is the default above 8 clients.  CORE_PROJECT_VARIANT=valu|mfma forces one for A/B runs.
+// so it is the default above 8 clients.  CORE_PROJECT_VARIANT=valu|mfma forces one for A/B runs
+// (and =q forces the lanes-over-q kernel, see make_plan).
 bool use_mfma_projection(uint32_t nc)
 {
     const char* v = getenv("CORE_PROJECT_VARIANT");
@@ -110,15 +148,16 @@ bool use_mfma_projection(uint32_t nc)
 }
 
 int validate_compress(uint64_t d, uint32_t m, uint32_t n, const void* G, core_dtype dt, uint64_t ld,
-                      const float* P, const float* pbar, const void* ws, size_t ws_bytes, Plan& plan)
+                      const float* P, const float* pbar, const void* ws, size_t ws_bytes, Plan& plan,
+                      bool allow_qmode = true)
 {
     if (!G || !pbar || !ws) return CORE_ERR_INVALID_ARGUMENT;
     if (dt != CORE_DTYPE_F32 && dt != CORE_DTYPE_BF16) return CORE_ERR_INVALID_ARGUMENT;
     if (ld < d) return CORE_ERR_INVALID_ARGUMENT;
-    if (!make_plan(d, m, n, plan)) return CORE_ERR_INVALID_ARGUMENT;
+    if (!make_plan(d, m, n, allow_qmode, plan)) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(G, dt == CORE_DTYPE_F32 ? 4 : 2)) return CORE_ERR_MISALIGNED;
     if (!aligned_to(pbar, 4) || (P && !aligned_to(P, 4)) || !aligned_to(ws, 16)) return CORE_ERR_MISALIGNED;
-    if (ws_bytes < plan.total) return CORE_ERR_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < workspace_bytes(d, m, n)) return CORE_ERR_WORKSPACE_TOO_SMALL;
     return CORE_OK;
 }
 
@@ -145,9 +184,22 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     a.jtiles = plan.jtiles; a.nchunks = plan.nchunks; a.tiles_per_chunk = plan.tiles_per_chunk;
     a.part = part;
     a.xi_store = xi_store;
-    const uint32_t blocks = (uint32_t)(ceil_div(plan.nchunks, 8) * 8 * plan.jtiles);
     const bool bf16 = (dt == CORE_DTYPE_BF16);
 
+    if (plan.qmode) {
+        const uint32_t blocks = plan.nchunks * plan.jtiles;
+        for (uint32_t c0 = 0; c0 < n; c0 += 8) {
+            const uint32_t nc = (n - c0 < 8u) ? (n - c0) : 8u;
+            a.c0 = c0; a.nc = nc;
+            hipError_t e;
+            if (nc <= 1)      e = launch_project_q<1>(a, bf16, blocks, st);
+            else if (nc <= 2) e = launch_project_q<2>(a, bf16, blocks, st);
+            else if (nc <= 4) e = launch_project_q<4>(a, bf16, blocks, st);
+            else              e = launch_project_q<8>(a, bf16, blocks, st);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+    } else {
+    const uint32_t blocks = (uint32_t)(ceil_div(plan.nchunks, 8) * 8 * plan.jtiles);
     for (uint32_t c0 = 0; c0 < n; c0 += kMaxClientsPerPass) {
         const uint32_t nc = (n - c0 < kMaxClientsPerPass) ? (n - c0) : kMaxClientsPerPass;
         a.c0 = c0; a.nc = nc;
@@ -166,7 +218,9 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         else              e = launch_project<16>(a, bf16, store, blocks, st);
         if (e != hipSuccess) return hip_fail(e);
     }
+    }
 
+    const uint64_t E = (uint64_t)n * m;
     hipLaunchKernelGGL(reduce_chunks_kernel, dim3((uint32_t)ceil_div(m, 32), n, plan.Z), dim3(kThreads), 0, st,
                        part, m, n, plan.nchunks, psum);
     hipError_t e = hipGetLastError();
@@ -273,12 +327,7 @@ const char* core_strerror(int code)
 
 int core_last_hip_error(void) { return g_last_hip_error; }
 
-size_t core_workspace_bytes(uint64_t d, uint32_t m, uint32_t n)
-{
-    Plan p;
-    if (!make_plan(d, m, n, p)) return 0;
-    return p.total;
-}
+size_t core_workspace_bytes(uint64_t d, uint32_t m, uint32_t n) { return workspace_bytes(d, m, n); }
 
 int core_compress_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
                           const void* G, core_dtype dt, uint64_t ld, float* P, float* pbar,
@@ -360,7 +409,7 @@ int core_compress_batched_store_xi(uint64_t seed, uint64_t round, uint64_t d, ui
                                    core_stream stream)
 {
     Plan plan;
-    int rc = validate_compress(d, m, n, G, dt, ld, P, pbar, ws, ws_bytes, plan);
+    int rc = validate_compress(d, m, n, G, dt, ld, P, pbar, ws, ws_bytes, plan, false);
     if (rc != CORE_OK) return rc;
     if (!xi) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(xi, 16)) return CORE_ERR_MISALIGNED;
@@ -390,7 +439,7 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
                             float* xi, size_t xi_buf_bytes, void* ws, size_t ws_bytes, core_stream stream)
 {
     Plan plan;
-    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan, false);
     if (rc != CORE_OK) return rc;
     if ((rc = validate_reconstruct(d, m, pbar, gtilde)) != CORE_OK) return rc;
     if (!xi) return CORE_ERR_INVALID_ARGUMENT;

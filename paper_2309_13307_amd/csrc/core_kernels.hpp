@@ -243,6 +243,87 @@ __global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
     }
 }
 
+// Projection for few vectors or little work (m < 64, or too few tiles to fill the chip with the
+// lanes-over-j kernels above).  Lanes run over the Philox block q, as in the reconstruction; a block
+// owns kQJ consecutive vectors and a chunk of 1024-coordinate tiles.  Each thread keeps G for its 4
+// coordinates in registers, generates the kQJ normals blocks, and accumulates its share of the kQJ x NC
+// sums; the sums are combined across the block once per chunk (wave butterfly, then LDS in wave order).
+// All lanes do useful work whatever m is, and a tiny problem is spread over many short blocks.
+constexpr int kQJ = 4;
+
+template <int NC, bool BF16>
+__global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
+{
+    __shared__ float red[kThreads / 64][kQJ * NC];
+    const uint32_t t = threadIdx.x;
+    const uint32_t jg = blockIdx.x % a.jtiles;          // a.jtiles = groups of kQJ vectors here
+    const uint32_t chunk = blockIdx.x / a.jtiles;
+    const uint32_t j0 = jg * kQJ;
+
+    const uint64_t qtile = (uint64_t)kThreads * 4;      // coordinates per tile
+    const uint64_t tiles_total = (a.d + qtile - 1) / qtile;
+    const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk;
+    uint64_t tile_end = tile_begin + a.tiles_per_chunk;
+    if (tile_end > tiles_total) tile_end = tiles_total;
+
+    Generator<2, 3> gen;
+    gen.init(a.k0, a.k1, a.r0, a.r1);
+
+    float acc[kQJ][NC];
+#pragma unroll
+    for (int jj = 0; jj < kQJ; ++jj)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[jj][c] = 0.0f;
+
+    for (uint64_t tl = tile_begin; tl < tile_end; ++tl) {
+        const uint64_t q = tl * kThreads + t;
+        const uint64_t i = 4 * q;
+        float g[NC][4];
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float v = 0.0f;
+                if (i + k < a.d && (uint32_t)c < a.nc) v = load_g<BF16>(a.G, (uint64_t)(a.c0 + c) * a.ld + i + k);
+                g[c][k] = v;
+            }
+#pragma unroll
+        for (int jj = 0; jj < kQJ; ++jj) {
+            if (j0 + jj >= a.m) break;                   // block-uniform
+            float z0, z1, z2, z3;
+            gen.block((uint32_t)q, j0 + jj, z0, z1, z2, z3);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                acc[jj][c] = fmaf(z0, g[c][0], acc[jj][c]);
+                acc[jj][c] = fmaf(z1, g[c][1], acc[jj][c]);
+                acc[jj][c] = fmaf(z2, g[c][2], acc[jj][c]);
+                acc[jj][c] = fmaf(z3, g[c][3], acc[jj][c]);
+            }
+        }
+    }
+
+    // fixed-order combination: butterfly inside each wave, then waves 0..3 in order
+#pragma unroll
+    for (int jj = 0; jj < kQJ; ++jj)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            float v = acc[jj][c];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+            if ((t & 63u) == 0) red[t >> 6][jj * NC + c] = v;
+        }
+    __syncthreads();
+    if (t < (uint32_t)(kQJ * NC)) {
+        const uint32_t jj = t / NC, c = t % NC;
+        if (j0 + jj < a.m && c < a.nc) {
+            float tot = red[0][t];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) tot += red[w][t];
+            a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + j0 + jj] = kXiScale * tot;
+        }
+    }
+}
+
 // Cross-chunk sum (a4), stage A: psum[z][c][j] = sum over the chunks of slice z of part[k][c][j],
 // fp64, fixed order.  grid = (ceil(m/32), n, Z); block = 32 vectors x 8 interleaved sub-slices.
 // Chunk k belongs to slice k % Z and, inside it, to sub-slice (k / Z) % 8.

@@ -108,17 +108,27 @@ SHAPES = [
 ]
 
 
+@pytest.fixture(params=["default", "valu", "mfma", "q"])
+def variant(request, monkeypatch):
+    """Run a test once per projection kernel: the library's own choice, and each forced one."""
+    if request.param != "default":
+        monkeypatch.setenv("CORE_PROJECT_VARIANT", request.param)
+    else:
+        monkeypatch.delenv("CORE_PROJECT_VARIANT", raising=False)
+    return request.param
+
+
 @pytest.mark.parametrize("d,m,n", SHAPES)
-def test_ragged_shapes_fp32(d, m, n):
-    _say(f"ragged fp32 d={d} m={m} n={n}")
+def test_ragged_shapes_fp32(d, m, n, variant):
+    _say(f"ragged fp32 d={d} m={m} n={n} variant={variant}")
     rng = np.random.default_rng(1000 * d + 10 * m + n)
     G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
     _run_and_check(31 + d, m + n, G, m, what=f"d={d} m={m} n={n}")
 
 
 @pytest.mark.parametrize("d,m,n", [(5, 2, 1), (256, 64, 8), (1027, 70, 5), (9001, 260, 16), (40000, 33, 18)])
-def test_ragged_shapes_bf16(d, m, n):
-    _say(f"ragged bf16 d={d} m={m} n={n}")
+def test_ragged_shapes_bf16(d, m, n, variant):
+    _say(f"ragged bf16 d={d} m={m} n={n} variant={variant}")
     rng = np.random.default_rng(7000 * d + 10 * m + n)
     G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
     _run_and_check(77, d, G, m, what=f"bf16 d={d} m={m} n={n}")
@@ -230,7 +240,9 @@ def test_materialised_xi_variant(d, m, n, bf16):
     assert torch.equal(xi, xi2)
     norms = parity.row_norms(G_host)
     parity.check_projections(P.cpu().numpy(), P_ref, norms, d, m, "materialised P")
-    assert torch.equal(pbar, pbar2) and torch.equal(pbar, pbar3)
+    assert torch.equal(pbar, pbar2)
+    # the regenerating round may use another projection kernel (summation order differs)
+    assert parity.rel_l2(pbar3.cpu().numpy(), pbar.cpu().numpy()) < 2e-6
     parity.check_gtilde(gt.cpu().numpy(), gt_ref, "materialised end-to-end")
     assert torch.equal(gt, gt_from)
     # and it agrees with the regenerating path to fp32 rounding
@@ -319,9 +331,9 @@ def _random_shapes(count, seed):
 
 
 @pytest.mark.parametrize("d,m,n,bf16,pad", _random_shapes(24, 2024))
-def test_random_shapes(d, m, n, bf16, pad):
+def test_random_shapes(d, m, n, bf16, pad, variant):
     """Seeded random shapes, both input types, padded rows: every kernel template and tail."""
-    _say(f"random shape d={d} m={m} n={n} bf16={bf16} pad={pad}")
+    _say(f"random shape d={d} m={m} n={n} bf16={bf16} pad={pad} variant={variant}")
     rng = np.random.default_rng(d * 131 + m * 17 + n)
     full = torch.from_numpy((rng.standard_normal((n, d + pad)) * rng.uniform(1e-3, 10.0)).astype(np.float32)).to(DEV)
     if bf16:
