@@ -221,11 +221,20 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     }
 
     const uint64_t E = (uint64_t)n * m;
+    hipError_t e;
+    if (plan.nchunks <= 16) {
+        // few chunks: one kernel sums them and the clients
+        hipLaunchKernelGGL(reduce_clients_kernel<float>, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), 0, st,
+                           part, m, n, plan.nchunks, P, pbar);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+        return CORE_OK;
+    }
     hipLaunchKernelGGL(reduce_chunks_kernel, dim3((uint32_t)ceil_div(m, 32), n, plan.Z), dim3(kThreads), 0, st,
                        part, m, n, plan.nchunks, psum);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
-    hipLaunchKernelGGL(reduce_clients_kernel, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), 0, st,
+    hipLaunchKernelGGL(reduce_clients_kernel<double>, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), 0, st,
                        psum, m, n, plan.Z, P, pbar);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);

@@ -362,9 +362,11 @@ __global__ void __launch_bounds__(kThreads) reduce_chunks_kernel(const float* __
 }
 
 // Stage B: P[c][j] = sum_z psum[z][c][j]; the client mean of Eq. (tildefdef),
+// (with at most 16 chunks stage A is skipped and this kernel sums the fp32 partials directly)
 // pbar[j] = (1/n) sum_c P[c][j].  Block = 32 vectors x 8 client lanes (lane cl takes clients
 // cl, cl+8, ...); fp64, fixed order.
-__global__ void __launch_bounds__(kThreads) reduce_clients_kernel(const double* __restrict__ psum,
+template <typename T>   // double: slices from stage A; float: the partials themselves (few chunks)
+__global__ void __launch_bounds__(kThreads) reduce_clients_kernel(const T* __restrict__ psum,
                                                                   uint32_t m, uint32_t n, uint32_t Z,
                                                                   float* __restrict__ P,
                                                                   float* __restrict__ pbar)
@@ -377,9 +379,9 @@ __global__ void __launch_bounds__(kThreads) reduce_clients_kernel(const double* 
     double tot = 0.0;
     if (j < m) {
         for (uint32_t c = cl; c < n; c += 8) {
-            const double* src = psum + (uint64_t)c * m + j;
+            const T* src = psum + (uint64_t)c * m + j;
             double s = 0.0;
-            for (uint32_t z = 0; z < Z; ++z) s += src[(uint64_t)z * E];
+            for (uint32_t z = 0; z < Z; ++z) s += (double)src[(uint64_t)z * E];
             if (P) P[(uint64_t)c * m + j] = (float)s;
             tot += s;
         }
