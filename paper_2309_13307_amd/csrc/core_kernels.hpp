@@ -205,9 +205,14 @@ __global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
         __syncthreads();
         if (tl + 1 < tile_end) fetch(tl + 1);
 
-        mfma_f32x4 acc[NG];
+        // kSplit independent accumulator sets per client group: consecutive matrix instructions
+        // never wait for each other's result
+        constexpr int kSplit = (NG >= 4) ? 1 : (NG >= 2 ? 2 : 4);
+        mfma_f32x4 acc[kSplit][NG];
 #pragma unroll
-        for (int g = 0; g < NG; ++g) acc[g] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int sidx = 0; sidx < kSplit; ++sidx)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[sidx][g] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
         const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
 #pragma unroll 2
         for (int qq = 0; qq < kTile / 4; ++qq) {
@@ -218,16 +223,18 @@ __global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
             for (int g = 0; g < NG; ++g) gv[g] = *reinterpret_cast<const float4*>(&tile[4 * g + csub][4 * qq]);
             // coordinate-major order: consecutive instructions update different accumulators
 #pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z0, gv[g].x, acc[g], 0, 0, 0);
+            for (int g = 0; g < NG; ++g) acc[0][g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z0, gv[g].x, acc[0][g], 0, 0, 0);
 #pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z1, gv[g].y, acc[g], 0, 0, 0);
+            for (int g = 0; g < NG; ++g) acc[1 % kSplit][g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z1, gv[g].y, acc[1 % kSplit][g], 0, 0, 0);
 #pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z2, gv[g].z, acc[g], 0, 0, 0);
+            for (int g = 0; g < NG; ++g) acc[2 % kSplit][g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z2, gv[g].z, acc[2 % kSplit][g], 0, 0, 0);
 #pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z3, gv[g].w, acc[g], 0, 0, 0);
+            for (int g = 0; g < NG; ++g) acc[3 % kSplit][g] = __builtin_amdgcn_mfma_f32_4x4x1f32(z3, gv[g].w, acc[3 % kSplit][g], 0, 0, 0);
         }
 #pragma unroll
-        for (int g = 0; g < NG; ++g) outer[g] += acc[g];
+        for (int sidx = 0; sidx < kSplit; ++sidx)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) outer[g] += acc[sidx][g];
     }
 
     const uint32_t jrow = jt * kThreads + (t & ~3u);   // first of the 4 vectors this lane reports
