@@ -341,3 +341,56 @@ def test_random_shapes(d, m, n, bf16, pad, variant):
     G = full[:, :d] if pad else full
     assert G.stride(0) == d + pad
     _run_and_check(1000 + d, m * n, G, m, d=d, what=f"random d={d} m={m} n={n}")
+
+
+def test_streams_and_graph_capture():
+    """Entry points only enqueue on the given stream: they work on side streams, two streams with
+    their own scratch can run at once, and a captured HIP graph replays to the eager result."""
+    rng = np.random.default_rng(77)
+    d, m, n = 30000, 300, 8
+    _say(f"streams/graph d={d} m={m} n={n}")
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
+    ws0 = core.alloc_workspace(d, m, n)
+    ref_pbar, ref_gt = core.core_round(5, 1, G, m, ws=ws0)
+    ref_pbar2, ref_gt2 = core.core_round(5, 2, G, m, ws=ws0)
+    _sync()
+    # two side streams, each with its own scratch and outputs
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ws1, ws2 = core.alloc_workspace(d, m, n), core.alloc_workspace(d, m, n)
+    out1 = (torch.empty(m, device=DEV), torch.empty(d, device=DEV))
+    out2 = (torch.empty(m, device=DEV), torch.empty(d, device=DEV))
+    for _ in range(3):
+        with torch.cuda.stream(s1):
+            core.core_round(5, 1, G, m, pbar=out1[0], gtilde=out1[1], ws=ws1)
+        with torch.cuda.stream(s2):
+            core.core_round(5, 2, G, m, pbar=out2[0], gtilde=out2[1], ws=ws2)
+    _sync()
+    assert torch.equal(out1[0], ref_pbar) and torch.equal(out1[1], ref_gt)
+    assert torch.equal(out2[0], ref_pbar2) and torch.equal(out2[1], ref_gt2)
+    # graph capture: no allocation, no synchronisation, no memset nodes inside the library
+    gp, gg = torch.empty(m, device=DEV), torch.empty(d, device=DEV)
+    x = torch.zeros(d, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        core.core_round(5, 1, G, m, pbar=gp, gtilde=gg, ws=ws1)
+        core.core_reconstruct_update(5, 1, gp, 1.0 / m, 0.5, x, x)
+    for rep in range(3):
+        gp.zero_(); gg.zero_()
+        x.fill_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        # eager work between replays
+        tmp = (G.float() * 2).sum()
+        torch.cuda.synchronize()
+        assert torch.equal(gp, ref_pbar) and torch.equal(gg, ref_gt), f"replay {rep}"
+        assert parity.rel_l2((1.0 - x).cpu().numpy(), 0.5 * ref_gt.cpu().numpy()) < 1e-5
+        assert bool(torch.isfinite(tmp))
+
+
+@pytest.mark.parametrize("d,m,n", [(300, 20000, 2), (2000, 5, 100), (20000, 2100, 1)])
+def test_extreme_aspect_ratios(d, m, n, variant):
+    """Many vectors on a short gradient, many clients (several passes), one client on a long one."""
+    _say(f"aspect d={d} m={m} n={n} variant={variant}")
+    rng = np.random.default_rng(d + m + n)
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
+    _run_and_check(404, 7, G, m, what=f"aspect d={d} m={m} n={n}")
