@@ -145,6 +145,66 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
                       float *gtilde,
                       void *ws, size_t ws_bytes, core_stream stream);
 
+/* ---- CORE-GD for non-convex objectives (Algorithm 3, Section 5) -----------------------------
+ * An iteration of Algorithm 3 is a round of Algorithm 2 plus three things: a scalar p formed from
+ * the combined projections, a step size h_k chosen from p (Option I) or from constants
+ * (Option II), and a comparison step that keeps x^k unless the trial point
+ * xt = x^k - h_k * gtilde has a strictly smaller objective value.  None of them needs the host
+ * to read device memory: p, h_k, the two objective values and the accept flag all stay on the
+ * device, so the iterations can be queued back to back.
+ *
+ * The statistic.  The printed definition of p (a plain average of the summed projections, with
+ * the machine and vector indices exchanged) cannot give the event p >= 2 |grad f(x^k)| that the
+ * proof of Theorem 5.1 uses; since each combined projection is N(0, |grad f|^2) (lemma on the
+ * law of C(a)), the library forms the norm estimate
+ *   p = c * sqrt((1/m) sum_j pbar[j]^2),        c >= 2 chosen by the caller,
+ * for which m (p/c)^2 / |grad f|^2 is chi-square with m degrees of freedom.
+ *
+ * core_nonconvex_step: Option I of Algorithm 3,
+ *   h = min{ m/(16 r1), (1/1600) H^(-1/2) p^(-1/2) d^(-3/4) m^(3/4) }     (first term if p = 0)
+ *   pbar [m] device fp32 (in);  p_out, h_out: device fp32 scalars (out; p_out may be NULL)
+ *   r1 > 0 (bound on the trace of the Hessian), H > 0 (Lipschitz constant of the Hessian), c > 0;
+ *   the two constant factors are evaluated on the host in fp64 and rounded to fp32 once. */
+int core_nonconvex_step(uint64_t d, uint32_t m, const float *pbar, float c, double r1, double H,
+                        float *p_out, float *h_out, core_stream stream);
+
+/* Option II of Algorithm 3: h = min{ m/(16 r1), (1/1600) H^(-1/2) (L Delta)^(-1/4) d^(-3/4) m^(3/4) }.
+ * Pure host arithmetic (fp64); h is a host pointer.  Use the result with
+ * core_reconstruct_update / core_round_update, which take h by value. */
+int core_step_size_option2(uint64_t d, uint32_t m, double r1, double H, double L, double Delta,
+                           double *h);
+
+/* Trial point of Algorithm 3 with the step read from device memory:
+ *   x_trial[i] = x[i] - (*h) * scale * sum_j pbar[j] xi_j[i]
+ *   h device fp32 scalar (e.g. h_out of core_nonconvex_step, written earlier on the same stream)
+ *   x [d] device fp32 (in);  x_trial [d] device fp32 (out), a different buffer from x
+ *   gtilde [d] device fp32 out or NULL; must not alias x or x_trial. */
+int core_reconstruct_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m,
+                           const float *pbar, float scale, const float *h,
+                           const float *x, float *x_trial,
+                           float *gtilde, core_stream stream);
+
+/* core_compress_batched(P = NULL), core_nonconvex_step and core_reconstruct_trial(scale = 1/m):
+ * everything of one iteration of Algorithm 3 (Option I) between the evaluation of the client
+ * gradients and the evaluation of f at the trial point.  Outputs: pbar [m], p_out (may be NULL),
+ * h_out, x_trial [d], gtilde [d] (may be NULL). */
+int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                     const void *G, core_dtype dt, uint64_t ld,
+                     float *pbar, float c, double r1, double H, float *p_out, float *h_out,
+                     const float *x, float *x_trial, float *gtilde,
+                     void *ws, size_t ws_bytes, core_stream stream);
+
+/* Comparison step of Algorithm 3: x^{k+1} = argmin over {x^k, xt} of f.  With the two objective
+ * values supplied by the caller as device scalars,
+ *   if (*f_trial < *f_cur) { x[0..d) = x_trial[0..d); *f_cur = *f_trial; *accepted = 1; }
+ *   else                   { *accepted = 0; }            (ties and NaN keep x)
+ *   f_cur device fp32 scalar (in/out), f_trial device fp32 scalar (in)
+ *   x [d] device fp32 (in/out), x_trial [d] device fp32 (in), a different buffer from x
+ *   accepted: device int32 scalar (out, required: it carries the decision between the two
+ *   kernels of this call). */
+int core_accept_trial(uint64_t d, float *f_cur, const float *f_trial,
+                      float *x, const float *x_trial, int32_t *accepted, core_stream stream);
+
 /* ---- materialised-Xi comparison variant ---------------------------------------------------
  * The matrix Xi = [xi_1 ... xi_m]^T of the paper's privacy appendix (p = Xi a) is normally never
  * stored.  These entry points store it once, while projecting, and read it back to reconstruct,

@@ -28,6 +28,8 @@ EXPORTS = (
     "core_compress_batched", "core_reconstruct", "core_round", "core_debug_philox", "core_debug_xi",
     "core_xi_bytes", "core_compress_batched_store_xi", "core_reconstruct_from_xi",
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
+    "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
+    "core_accept_trial",
 )
 
 
@@ -78,6 +80,18 @@ def load_library() -> ctypes.CDLL:
     L.core_round_update.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, f32, vp, vp, vp, f32, vp, vp,
                                     vp, sz, vp]
     L.core_round_update.restype = i32
+    f64 = ctypes.c_double
+    L.core_nonconvex_step.argtypes = [u64, u32, vp, f32, f64, f64, vp, vp, vp]
+    L.core_nonconvex_step.restype = i32
+    L.core_step_size_option2.argtypes = [u64, u32, f64, f64, f64, f64, ctypes.POINTER(f64)]
+    L.core_step_size_option2.restype = i32
+    L.core_reconstruct_trial.argtypes = [u64, u64, u64, u32, vp, f32, vp, vp, vp, vp, vp]
+    L.core_reconstruct_trial.restype = i32
+    L.core_round_trial.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, f32, f64, f64, vp, vp, vp, vp,
+                                   vp, vp, sz, vp]
+    L.core_round_trial.restype = i32
+    L.core_accept_trial.argtypes = [u64, vp, vp, vp, vp, vp, vp]
+    L.core_accept_trial.restype = i32
     L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     L.core_debug_philox.restype = i32
     L.core_debug_xi.argtypes = [u64, u64, u32, u64, u64, vp, vp]
@@ -236,6 +250,62 @@ def core_round_update(seed: int, rnd: int, G: torch.Tensor, m: int, h: float, y:
                                           one_minus_beta, _ptr(y_next), _ptr(gtilde), ws.data_ptr(),
                                           ws.numel(), _stream())
     _check(rc, "core_round_update")
+
+
+def core_nonconvex_step(d: int, pbar: torch.Tensor, c: float, r1: float, H: float,
+                        p_out: torch.Tensor | None, h_out: torch.Tensor) -> None:
+    """Option I of Algorithm 3: p_out = c * sqrt(mean pbar^2), h_out = the step size (device scalars)."""
+    _require_cuda(pbar, p_out, h_out)
+    rc = load_library().core_nonconvex_step(d, pbar.numel(), pbar.data_ptr(), c, r1, H, _ptr(p_out),
+                                            h_out.data_ptr(), _stream())
+    _check(rc, "core_nonconvex_step")
+
+
+def core_step_size_option2(d: int, m: int, r1: float, H: float, L: float, Delta: float) -> float:
+    """Option II of Algorithm 3 (host arithmetic, fp64)."""
+    out = ctypes.c_double(0.0)
+    rc = load_library().core_step_size_option2(d, m, r1, H, L, Delta, ctypes.byref(out))
+    _check(rc, "core_step_size_option2")
+    return out.value
+
+
+def core_reconstruct_trial(seed: int, rnd: int, pbar: torch.Tensor, scale: float, h: torch.Tensor,
+                           x: torch.Tensor, x_trial: torch.Tensor, gtilde: torch.Tensor | None = None) -> None:
+    """x_trial = x - h * scale * sum_j pbar[j] xi_j with the step h read from device memory."""
+    _require_cuda(pbar, h, x, x_trial, gtilde)
+    rc = load_library().core_reconstruct_trial(seed, rnd, x.numel(), pbar.numel(), pbar.data_ptr(), scale,
+                                               h.data_ptr(), x.data_ptr(), x_trial.data_ptr(), _ptr(gtilde),
+                                               _stream())
+    _check(rc, "core_reconstruct_trial")
+
+
+def core_round_trial(seed: int, rnd: int, G: torch.Tensor, m: int, c: float, r1: float, H: float,
+                     x: torch.Tensor, x_trial: torch.Tensor, pbar: torch.Tensor, p_out: torch.Tensor | None,
+                     h_out: torch.Tensor, ws: torch.Tensor, gtilde: torch.Tensor | None = None,
+                     d: int | None = None) -> None:
+    """One iteration of Algorithm 3 (Option I) between the gradient evaluation and f(x_trial)."""
+    _require_cuda(G, x, x_trial, pbar, p_out, h_out, ws, gtilde)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    rc = load_library().core_round_trial(seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld,
+                                         pbar.data_ptr(), c, r1, H, _ptr(p_out), h_out.data_ptr(),
+                                         x.data_ptr(), x_trial.data_ptr(), _ptr(gtilde), ws.data_ptr(),
+                                         ws.numel(), _stream())
+    _check(rc, "core_round_trial")
+
+
+def core_accept_trial(f_cur: torch.Tensor, f_trial: torch.Tensor, x: torch.Tensor, x_trial: torch.Tensor,
+                      accepted: torch.Tensor) -> None:
+    """Comparison step of Algorithm 3: x <- x_trial and f_cur <- f_trial iff f_trial < f_cur."""
+    _require_cuda(f_cur, f_trial, x, x_trial, accepted)
+    if accepted.dtype != torch.int32:
+        raise TypeError("accepted must be an int32 tensor")
+    rc = load_library().core_accept_trial(x.numel(), f_cur.data_ptr(), f_trial.data_ptr(), x.data_ptr(),
+                                          x_trial.data_ptr(), accepted.data_ptr(), _stream())
+    _check(rc, "core_accept_trial")
 
 
 def core_xi_bytes(d: int, m: int) -> int:

@@ -111,3 +111,59 @@ class DecentralizedRidgeCoreGD:
         for c in range(self.n):
             binding.core_reconstruct_update(self.seed, k, P[c], self.n / self.m, h / self.n,
                                             self.X[c], self.X[c])
+
+
+class RobustCoreGD:
+    """Algorithm 3 (CORE-GD for non-convex objectives, Section 5) on a robust-regression objective
+    f(x) = mean_i phi(a_i^T x - b_i), phi(t) = t^2 / (1 + t^2), rows split evenly over n machines.
+
+    The library does the round, the statistic p, the Option I step size, the trial point and the
+    comparison step; this harness evaluates the client gradients and f with torch.  Nothing in a
+    round reads device memory from the host, so rounds can be queued back to back."""
+
+    def __init__(self, A: np.ndarray, b: np.ndarray, n: int, m: int, seed: int, c: float = 4.0,
+                 device="cuda"):
+        rows, d = A.shape
+        assert rows % n == 0
+        self.A = torch.from_numpy(np.ascontiguousarray(A, dtype=np.float32)).to(device)
+        self.b = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(device)
+        self.A3 = self.A.view(n, rows // n, d)
+        self.n, self.m, self.seed, self.d, self.c = n, m, seed, d, c
+        self.rows_per = rows // n
+        self.x = torch.zeros(d, dtype=torch.float32, device=device)
+        self.x_trial = torch.empty_like(self.x)
+        self.ws = binding.alloc_workspace(d, m, n, device)
+        self.pbar = torch.empty(m, dtype=torch.float32, device=device)
+        self.p = torch.zeros(1, dtype=torch.float32, device=device)
+        self.h = torch.zeros(1, dtype=torch.float32, device=device)
+        self.accepted = torch.zeros(1, dtype=torch.int32, device=device)
+        self.f_cur = self.loss(self.x).reshape(1).clone()
+        self.f_trial = torch.zeros(1, dtype=torch.float32, device=device)
+        # bounds for this objective: phi'' <= 2, |phi'''| <= 4.67
+        A64 = np.asarray(A, dtype=np.float64)
+        lam_max = float(np.linalg.eigvalsh(A64.T @ A64 / rows)[-1])
+        row2 = (A64 * A64).sum(axis=1)
+        self.r1 = 2.0 * float(row2.mean())
+        self.L = 2.0 * lam_max
+        self.H = 4.67 * float(np.sqrt(row2.max())) * lam_max
+
+    def loss(self, x: torch.Tensor) -> torch.Tensor:
+        t = self.A @ x - self.b
+        t2 = t * t
+        return (t2 / (1.0 + t2)).mean()
+
+    def client_gradients(self, x: torch.Tensor) -> torch.Tensor:
+        t = self.A @ x - self.b
+        w = (2.0 * t / (1.0 + t * t) ** 2).view(self.n, -1, 1)
+        return (torch.bmm(self.A3.transpose(1, 2), w).squeeze(-1) / self.rows_per).contiguous()
+
+    def round(self, k: int, r1: float | None = None, H: float | None = None,
+              gtilde: torch.Tensor | None = None) -> torch.Tensor:
+        """One iteration of Algorithm 3, Option I; returns the client gradients it used."""
+        G = self.client_gradients(self.x)
+        binding.core_round_trial(self.seed, k, G, self.m, self.c, self.r1 if r1 is None else r1,
+                                 self.H if H is None else H, self.x, self.x_trial, self.pbar, self.p,
+                                 self.h, self.ws, gtilde=gtilde)
+        self.f_trial.copy_(self.loss(self.x_trial).reshape(1))
+        binding.core_accept_trial(self.f_cur, self.f_trial, self.x, self.x_trial, self.accepted)
+        return G

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#include <cmath>
 
 #include "../../include/core.h"
 #include "core_kernels.hpp"
@@ -247,6 +248,7 @@ struct UpdateArgs {
     const float* x_cur = nullptr;
     float* y_next = nullptr;
     float h = 0.0f, omb = 0.0f;
+    const float* h_dev = nullptr;
 };
 
 int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
@@ -258,9 +260,10 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
     bool vec = !gtilde || aligned_to(gtilde, 16);
     a.y = nullptr; a.x_new = nullptr; a.x_cur = nullptr; a.y_next = nullptr; a.h = 0.0f; a.omb = 0.0f;
+    a.h_dev = nullptr;
     if (up) {
         a.y = up->y; a.x_new = up->x_new; a.x_cur = up->x_cur; a.y_next = up->y_next;
-        a.h = up->h; a.omb = up->omb;
+        a.h = up->h; a.omb = up->omb; a.h_dev = up->h_dev;
         vec = vec && aligned_to(up->y, 16) && aligned_to(up->x_new, 16) &&
               (!up->y_next || (aligned_to(up->y_next, 16) && aligned_to(up->x_cur, 16)));
     }
@@ -292,6 +295,37 @@ int validate_update(const float* y, const float* x_new, const float* x_cur, cons
     if (gtilde && (gtilde == x_new || gtilde == y || gtilde == x_cur)) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(y, 4) || !aligned_to(x_new, 4) || !aligned_to(x_cur, 4) || !aligned_to(y_next, 4) ||
         !aligned_to(gtilde, 4))
+        return CORE_ERR_MISALIGNED;
+    return CORE_OK;
+}
+
+int validate_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, double r1, double H,
+                            const float* p_out, const float* h_out)
+{
+    if (!pbar || !h_out || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!(c > 0.0f) || !(r1 > 0.0) || !(H > 0.0)) return CORE_ERR_INVALID_ARGUMENT;
+    if (h_out == p_out || h_out == pbar || p_out == pbar) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(pbar, 4) || !aligned_to(p_out, 4) || !aligned_to(h_out, 4)) return CORE_ERR_MISALIGNED;
+    return CORE_OK;
+}
+
+int enqueue_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, double r1, double H,
+                           float* p_out, float* h_out, hipStream_t st)
+{
+    const double first = (double)m / (16.0 * r1);
+    const double second = std::pow(H, -0.5) * std::pow((double)d, -0.75) * std::pow((double)m, 0.75) / 1600.0;
+    hipLaunchKernelGGL(nonconvex_step_kernel, dim3(1), dim3(kThreads), 0, st, pbar, m, c, (float)first,
+                       (float)second, p_out, h_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return CORE_OK;
+}
+
+int validate_trial(const float* h, const float* x, const float* x_trial, const float* gtilde)
+{
+    if (!h || !x || !x_trial || x == x_trial) return CORE_ERR_INVALID_ARGUMENT;
+    if (gtilde && (gtilde == x || gtilde == x_trial)) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(h, 4) || !aligned_to(x, 4) || !aligned_to(x_trial, 4) || !aligned_to(gtilde, 4))
         return CORE_ERR_MISALIGNED;
     return CORE_OK;
 }
@@ -408,6 +442,83 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
     UpdateArgs up;
     up.y = y; up.x_new = x_new; up.x_cur = x_cur; up.y_next = y_next; up.h = h; up.omb = one_minus_beta;
     return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, double r1, double H,
+                        float* p_out, float* h_out, core_stream stream)
+{
+    int rc = validate_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out);
+    if (rc != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    return enqueue_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out, (hipStream_t)stream);
+}
+
+int core_step_size_option2(uint64_t d, uint32_t m, double r1, double H, double L, double Delta, double* h)
+{
+    if (!h || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!(r1 > 0.0) || !(H > 0.0) || !(L > 0.0) || !(Delta > 0.0)) return CORE_ERR_INVALID_ARGUMENT;
+    const double first = (double)m / (16.0 * r1);
+    const double second = std::pow(H, -0.5) * std::pow(L * Delta, -0.25) * std::pow((double)d, -0.75) *
+                          std::pow((double)m, 0.75) / 1600.0;
+    *h = first < second ? first : second;
+    return CORE_OK;
+}
+
+int core_reconstruct_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
+                           float scale, const float* h, const float* x, float* x_trial, float* gtilde,
+                           core_stream stream)
+{
+    if (!pbar || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(pbar, 4)) return CORE_ERR_MISALIGNED;
+    int rc = validate_trial(h, x, x_trial, gtilde);
+    if (rc != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    UpdateArgs up;
+    up.y = x; up.x_new = x_trial; up.h_dev = h;
+    return enqueue_reconstruct(seed, round, d, m, pbar, scale, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n, const void* G,
+                     core_dtype dt, uint64_t ld, float* pbar, float c, double r1, double H, float* p_out,
+                     float* h_out, const float* x, float* x_trial, float* gtilde, void* ws, size_t ws_bytes,
+                     core_stream stream)
+{
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = validate_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out)) != CORE_OK) return rc;
+    if ((rc = validate_trial(h_out, x, x_trial, gtilde)) != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
+    if (rc != CORE_OK) return rc;
+    if ((rc = enqueue_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out, (hipStream_t)stream)) != CORE_OK)
+        return rc;
+    UpdateArgs up;
+    up.y = x; up.x_new = x_trial; up.h_dev = h_out;
+    return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_accept_trial(uint64_t d, float* f_cur, const float* f_trial, float* x, const float* x_trial,
+                      int32_t* accepted, core_stream stream)
+{
+    if (!f_cur || !f_trial || !x || !x_trial || !accepted || d == 0 || d > kMaxD)
+        return CORE_ERR_INVALID_ARGUMENT;
+    if (x == x_trial || f_cur == f_trial) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(f_cur, 4) || !aligned_to(f_trial, 4) || !aligned_to(x, 4) || !aligned_to(x_trial, 4) ||
+        !aligned_to(accepted, 4))
+        return CORE_ERR_MISALIGNED;
+    int rc = check_device();
+    if (rc != CORE_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(1), dim3(64), 0, st, f_cur, f_trial, accepted);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    const int vec = (aligned_to(x, 16) && aligned_to(x_trial, 16)) ? 1 : 0;
+    const uint32_t blocks = (uint32_t)ceil_div(ceil_div(d, 4), (uint64_t)kThreads);
+    hipLaunchKernelGGL(accept_copy_kernel, dim3(blocks), dim3(kThreads), 0, st, accepted, x, x_trial, d, vec);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return CORE_OK;
 }
 
 size_t core_xi_bytes(uint64_t d, uint32_t m) { return xi_bytes(d, m); }

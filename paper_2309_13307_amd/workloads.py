@@ -10,6 +10,7 @@ not available here; these inputs stand in for their shapes:
   config 3  d=2^20,        m=256,  n=8,  fp32   common vector + per-client perturbation
   config 4  d=25,557,032,  m=1024, n=8,  bf16   ResNet-50-sized gradient, 161 scale blocks
   config 5  d=124,439,808, m=4096, n=16, bf16   GPT-2-small-sized gradient, heavy tails, 5 rounds
+  robust    d=2048,        m=64,   n=8,  fp32   non-convex robust regression for Algorithm 3
 """
 from __future__ import annotations
 
@@ -130,3 +131,25 @@ def ridge_problem(rows: int = 8192, d: int = 4096, n: int = 8, m: int = 64, lam:
     x_true = np.random.default_rng(2).standard_normal(d)
     b = A @ x_true + 0.01 * np.random.default_rng(3).standard_normal(rows)
     return RidgeProblem(A.astype(np.float32), b.astype(np.float32), lam, n, m, 2, rounds)
+
+
+@dataclass
+class RobustProblem:
+    A: np.ndarray        # [rows, d] fp32
+    b: np.ndarray        # [rows] fp32, every 7th entry an outlier
+    n: int
+    m: int
+    seed: int
+    rounds: int
+
+
+def robust_problem(rows: int = 4096, d: int = 2048, n: int = 8, m: int = 64, rounds: int = 40) -> RobustProblem:
+    """Data of a robust-regression objective mean_i phi(a_i^T x - b_i) with a bounded, partly
+    concave phi (the non-convex stand-in for Section 5): Gaussian rows of norm about 1,
+    b = A x_true + 0.1 N(0,1), and +5 added to every 7th entry so that negative curvature occurs."""
+    rng = np.random.default_rng(50)
+    A = rng.standard_normal((rows, d)) / np.sqrt(d)
+    x_true = rng.standard_normal(d)
+    b = A @ x_true + 0.1 * rng.standard_normal(rows)
+    b[::7] += 5.0
+    return RobustProblem(A.astype(np.float32), b.astype(np.float32), n, m, 9, rounds)

@@ -19,6 +19,15 @@ int main(void)
     if (core_xi_bytes(5, 3) != 2u * 3u * 16u) return 7;
     if (strlen(core_strerror(CORE_ERR_WORKSPACE_TOO_SMALL)) == 0) return 8;
     if (core_last_hip_error() != 0) return 9;
+    {
+        double h = 0.0;
+        if (core_step_size_option2(16, 16, 1e-9, 1.0, 2.0, 8.0, &h) != CORE_OK) return 10;
+        if (h < 0.99 / 3200.0 || h > 1.01 / 3200.0) return 11;
+        if (core_accept_trial(16, dummy, dummy + 1, dummy, dummy, NULL, NULL) != CORE_ERR_INVALID_ARGUMENT)
+            return 12;
+        if (core_nonconvex_step(16, 4, dummy, 4.0f, -1.0, 1.0, NULL, dummy + 1, NULL)
+            != CORE_ERR_INVALID_ARGUMENT) return 13;
+    }
     puts("c client ok");
     return 0;
 }

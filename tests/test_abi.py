@@ -130,6 +130,53 @@ def test_materialised_variant_arguments():
     assert h(1, 0, 1024, 16, 4, FAKE, 0, 1024, None, FAKE, None, xb, FAKE, wsb, None) == E.ERR_INVALID_ARGUMENT
 
 
+def test_nonconvex_entry_points_arguments():
+    import ctypes
+    L = core.load_library()
+    E = binding
+    st = L.core_nonconvex_step
+    assert st(1024, 16, None, 4.0, 1.0, 1.0, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 4.0, 1.0, 1.0, FAKE + 64, None, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 0.0, 1.0, 1.0, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 4.0, 0.0, 1.0, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 4.0, 1.0, -1.0, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 4.0, 1.0, float("nan"), FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 0, FAKE, 4.0, 1.0, 1.0, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 4.0, 1.0, 1.0, FAKE + 64, FAKE + 64, None) == E.ERR_INVALID_ARGUMENT
+    assert st(1024, 16, FAKE, 4.0, 1.0, 1.0, FAKE + 64, FAKE + 130, None) == E.ERR_MISALIGNED
+    tr = L.core_reconstruct_trial
+    assert tr(1, 0, 16, 4, FAKE, 0.25, None, FAKE + 64, FAKE + 128, None, None) == E.ERR_INVALID_ARGUMENT
+    assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 64, None, None) == E.ERR_INVALID_ARGUMENT
+    assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 128, FAKE + 64, None) == E.ERR_INVALID_ARGUMENT
+    assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 33, FAKE + 64, FAKE + 128, None, None) == E.ERR_MISALIGNED
+    assert tr(1, 0, 0, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 128, None, None) == E.ERR_INVALID_ARGUMENT
+    ac = L.core_accept_trial
+    assert ac(16, None, FAKE + 4, FAKE + 64, FAKE + 128, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
+    assert ac(16, FAKE, FAKE + 4, FAKE + 64, FAKE + 64, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
+    assert ac(16, FAKE, FAKE + 4, FAKE + 64, FAKE + 128, None, None) == E.ERR_INVALID_ARGUMENT
+    assert ac(0, FAKE, FAKE + 4, FAKE + 64, FAKE + 128, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
+    assert ac(16, FAKE, FAKE + 4, FAKE + 66, FAKE + 128, FAKE + 8, None) == E.ERR_MISALIGNED
+    wsb = core.core_workspace_bytes(1024, 16, 4)
+    rt = L.core_round_trial
+    ok_args = [1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE + 4096, 4.0, 1.0, 1.0, FAKE + 8192, FAKE + 8196,
+               FAKE + 16384, FAKE + 32768, None, FAKE + 65536, wsb, None]
+    bad = list(ok_args); bad[13] = None
+    assert rt(*bad) == E.ERR_INVALID_ARGUMENT
+    bad = list(ok_args); bad[15] = bad[14]
+    assert rt(*bad) == E.ERR_INVALID_ARGUMENT
+    bad = list(ok_args); bad[18] = wsb - 1
+    assert rt(*bad) == E.ERR_WORKSPACE_TOO_SMALL
+    bad = list(ok_args); bad[10] = 0.0
+    assert rt(*bad) == E.ERR_INVALID_ARGUMENT
+    # Option II is host arithmetic: hand values (16^(3/4) = 8, 16^(-1/4) = 1/2)
+    assert abs(core.core_step_size_option2(16, 16, 1e-9, 1.0, 2.0, 8.0) - 1 / 3200) < 1e-18
+    assert abs(core.core_step_size_option2(16, 1, 1e-9, 4.0, 1.0, 1.0) - 1 / 25600) < 1e-19
+    assert core.core_step_size_option2(16, 8, 1e6, 1.0, 1.0, 1.0) == 8 / 16e6
+    out = ctypes.c_double(0.0)
+    assert L.core_step_size_option2(16, 8, 1.0, 1.0, 0.0, 1.0, ctypes.byref(out)) == E.ERR_INVALID_ARGUMENT
+    assert L.core_step_size_option2(16, 8, 1.0, 1.0, 1.0, 1.0, None) == E.ERR_INVALID_ARGUMENT
+
+
 def test_header_compiles_and_links_from_plain_c(tmp_path):
     import shutil
     import subprocess
