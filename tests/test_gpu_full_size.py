@@ -47,13 +47,12 @@ def _sampled_check(case, rnd, pbar, gtilde, jidx, nblocks_sampled, what):
     rng = np.random.default_rng(99 + rnd)
     nblk = (d + 3) // 4
     blocks = np.unique(np.concatenate([[0, nblk - 1, nblk // 2], rng.integers(0, nblk, nblocks_sampled)]))
-    gt = gtilde.cpu().numpy()
     ref = np.empty((len(blocks), 4))
     got = np.empty((len(blocks), 4))
     for t, q in enumerate(blocks):
         cnt = min(4, d - 4 * int(q))
         ref[t, :cnt] = oracle.reconstruct(case.seed, rnd, pbar_gpu, 1.0 / m, 4 * int(q), cnt)
-        got[t, :cnt] = gt[4 * int(q):4 * int(q) + cnt]
+        got[t, :cnt] = gtilde[4 * int(q):4 * int(q) + cnt].cpu().numpy()   # only the sampled block leaves the device
         ref[t, cnt:] = got[t, cnt:] = 0.0
     parity.check_gtilde(got.ravel(), ref.ravel(), what + " gtilde (sampled blocks)")
 
@@ -99,3 +98,77 @@ def test_config5_full_size_sampled():
     pb_cold, gt_cold = core.core_round(case.seed, 4, case.G, case.m, ws=ws)
     torch.cuda.synchronize()
     assert torch.equal(pb_cold, pbar) and torch.equal(gt_cold, gtilde)
+
+
+@pytest.mark.timeout(600)
+def test_dimension_above_2_32_dense():
+    """d just above 2^32 with a dense gradient: coordinate indices no longer fit 32 bits, and the
+    fp32 chains inside a chunk are at their capped length.  Two projection columns over the full
+    d (about 25 s each for the oracle) and sampled reconstruction blocks."""
+    d, m, n, seed, rnd = (1 << 32) + 1027, 256, 1, 29, 2
+    free, _ = torch.cuda.mem_get_info()
+    need = 2 * d + 4 * d + 4 * (1 << 30) + core.core_workspace_bytes(d, m, n) + (2 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of device memory")
+    _say(f"dense d={d} m={m} n={n} bf16")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(3232)
+    G = torch.empty((n, d), dtype=torch.bfloat16, device=DEV)
+    step = 1 << 28
+    for i0 in range(0, d, step):       # drawn in slices: a whole fp32 temporary would be 17 GB
+        cnt = min(step, d - i0)
+        G[0, i0:i0 + cnt] = (0.01 * torch.randn(cnt, generator=gen, device=DEV)).to(torch.bfloat16)
+    case = workloads.RoundCase("dense_2_32", d, m, n, seed, (rnd,), G)
+    ws = core.alloc_workspace(d, m, n, DEV)
+    pbar = torch.empty(m, dtype=torch.float32, device=DEV)
+    gtilde = torch.empty(d, dtype=torch.float32, device=DEV)
+    core.core_round(seed, rnd, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
+    torch.cuda.synchronize()
+    _say("dense d>2^32: round done, oracle columns 0 and 255 over the full d")
+    _sampled_check(case, rnd, pbar, gtilde, np.array([0, 255]), 24, "dense d>2^32")
+    del G, gtilde, ws, case
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+def test_largest_dimension():
+    """d = 2^34, the largest the library accepts (the Philox block index q = i/4 then reaches
+    2^32 - 1).  G is zero except in a few windows, so the oracle can form every projection exactly
+    from the windows alone, while the kernels still walk, generate and reduce over the whole range."""
+    d, m, n, seed, rnd = 1 << 34, 256, 1, 31, 3
+    free, _ = torch.cuda.mem_get_info()
+    need = 2 * d + 4 * d + core.core_workspace_bytes(d, m, n) + (2 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of device memory")
+    _say(f"largest dimension: d={d} m={m} n={n} bf16, G zero outside four windows")
+    windows = [(0, 4099), ((1 << 32) - 2051, 4102), (d // 2 + 1, 1000), (d - 5000, 5000)]
+    G = torch.zeros((n, d), dtype=torch.bfloat16, device=DEV)
+    rng = np.random.default_rng(34)
+    host = []
+    for i0, cnt in windows:
+        assert 0 <= i0 and i0 + cnt <= d
+        w = torch.from_numpy(rng.standard_normal(cnt).astype(np.float32)).to(DEV).to(torch.bfloat16)
+        G[0, i0:i0 + cnt] = w
+        host.append(w.float().cpu().numpy().astype(np.float64))
+    ws = core.alloc_workspace(d, m, n, DEV)
+    pbar = torch.empty(m, dtype=torch.float32, device=DEV)
+    gtilde = torch.empty(d, dtype=torch.float32, device=DEV)
+    core.core_round(seed, rnd, G, m, pbar=pbar, gtilde=gtilde, ws=ws)
+    torch.cuda.synchronize()
+    _say("largest dimension: round done, checking against the oracle")
+    # projections: every vector, from the windows
+    pbar_ref = np.zeros(m)
+    for (i0, cnt), g in zip(windows, host):
+        for j in range(m):
+            pbar_ref[j] += float(g @ oracle.xi_range(seed, rnd, j, i0, cnt))
+    norm = np.sqrt(sum(float(g @ g) for g in host))
+    pbar_gpu = pbar.cpu().numpy().astype(np.float64)
+    parity.check_projections(pbar_gpu[None, :], pbar_ref[None, :], np.array([norm]), d, m, f"d={d} pbar")
+    # reconstruction: windows at the start, around 2^32, in the middle and at the very end
+    for i0, cnt in [(0, 64), ((1 << 32) - 32, 64), (d // 2 - 16, 40), (d - 37, 37),
+                    (int(rng.integers(0, d - 64)) & ~3, 64)]:
+        ref = oracle.reconstruct(seed, rnd, pbar_gpu, 1.0 / m, i0, cnt)
+        got = gtilde[i0:i0 + cnt].cpu().numpy()
+        parity.check_gtilde(got, ref, f"d={d} gtilde[{i0}:{i0 + cnt}]")
+    del G, gtilde, ws
+    torch.cuda.empty_cache()
