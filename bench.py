@@ -57,7 +57,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(case, d_s=1 << 20, m_s=128):
+def cpu_baseline(case, d_s=1 << 20, m_s=256):
     """The oracle as it stands, one thread, on the first d_s coordinates x m_s vectors x all clients."""
     import oracle
     d_s = min(d_s, case.d)
