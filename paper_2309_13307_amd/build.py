@@ -7,6 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libcore_hip.so")
+PROBE_PATH = os.path.join(_HERE, "issue_probe")   # standalone VALU issue-cost microbenchmark
 
 SOURCES = ["core_api.hip"]
 HEADERS = ["core_rng.hpp", "core_kernels.hpp"]
@@ -40,5 +41,19 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_issue_probe(verbose: bool = False) -> str:
+    """Compile csrc/issue_probe.hip into the standalone executable `issue_probe`."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc] + flags + ["-o", PROBE_PATH, os.path.join(CSRC, "issue_probe.hip")]
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return PROBE_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_issue_probe(verbose=True))

@@ -4,7 +4,8 @@
 // the reconstruction kernels regenerate identical values and Xi never exists in memory.
 //
 // Written for gfx950.  Measured issue costs that shape this code (cycles per wave64
-// instruction per SIMD): plain two-operand VALU ops with VGPR/literal operands ~2.4,
+// instruction per SIMD): plain two-operand VALU ops with VGPR/literal operands ~2.4 (also
+// v_fma / v_bitop3 when src0 and src1 sit in different VGPR banks, as the Philox xors do),
 // the same ops with an SGPR operand ~4.4, v_mad_u64_u32 ~4.9 (v_mul_lo + v_mul_hi ~9),
 // v_cvt ~4.3, transcendentals (v_log/v_sqrt/v_sin/v_cos) ~8.2.  Hence: one 64-bit
 // multiply-add per Philox product, literals for the multipliers, round keys and constants of
