@@ -128,7 +128,8 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
  *   gtilde [d] device fp32 out, or NULL when the estimate itself is not wanted; must not alias
  *           the other buffers.
  * Every element is read before the same thread writes it, which is what makes the stated
- * aliasing safe. */
+ * aliasing safe.  "The same buffer" means the same address: ranges that overlap at different
+ * addresses are rejected with CORE_ERR_INVALID_ARGUMENT, here and in the Algorithm 3 entry points. */
 int core_reconstruct_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m,
                             const float *pbar, float scale, float h,
                             const float *y, float *x_new,

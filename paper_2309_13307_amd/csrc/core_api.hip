@@ -292,13 +292,30 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     return CORE_OK;
 }
 
-int validate_update(const float* y, const float* x_new, const float* x_cur, const float* y_next,
+// [a, a + na floats) and [b, b + nb floats) share at least one element (null never does)
+bool intersects(const float* a, uint64_t na, const float* b, uint64_t nb)
+{
+    if (!a || !b) return false;
+    const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + (uintptr_t)nb * sizeof(float) && pb < pa + (uintptr_t)na * sizeof(float);
+}
+bool intersects(const float* a, const float* b, uint64_t count) { return intersects(a, count, b, count); }
+
+// the two ranges intersect without being the same range (an in-place alias is element-wise safe,
+// a shifted one is not)
+bool overlaps_shifted(const float* a, const float* b, uint64_t count) { return a != b && intersects(a, b, count); }
+
+int validate_update(uint64_t d, const float* y, const float* x_new, const float* x_cur, const float* y_next,
                     const float* gtilde)
 {
     if (!y || !x_new) return CORE_ERR_INVALID_ARGUMENT;
     if ((x_cur == nullptr) != (y_next == nullptr)) return CORE_ERR_INVALID_ARGUMENT;
-    if (y_next && (y_next == x_new || y_next == gtilde)) return CORE_ERR_INVALID_ARGUMENT;
-    if (gtilde && (gtilde == x_new || gtilde == y || gtilde == x_cur)) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects(y_next, x_new, d) || intersects(y_next, gtilde, d)) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects(gtilde, x_new, d) || intersects(gtilde, y, d) || intersects(gtilde, x_cur, d))
+        return CORE_ERR_INVALID_ARGUMENT;
+    if (overlaps_shifted(y, x_new, d) || overlaps_shifted(x_cur, x_new, d) || overlaps_shifted(y_next, x_cur, d) ||
+        overlaps_shifted(y_next, y, d))
+        return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(y, 4) || !aligned_to(x_new, 4) || !aligned_to(x_cur, 4) || !aligned_to(y_next, 4) ||
         !aligned_to(gtilde, 4))
         return CORE_ERR_MISALIGNED;
@@ -327,10 +344,11 @@ int enqueue_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, d
     return CORE_OK;
 }
 
-int validate_trial(const float* h, const float* x, const float* x_trial, const float* gtilde)
+int validate_trial(uint64_t d, const float* h, const float* x, const float* x_trial, const float* gtilde)
 {
-    if (!h || !x || !x_trial || x == x_trial) return CORE_ERR_INVALID_ARGUMENT;
-    if (gtilde && (gtilde == x || gtilde == x_trial)) return CORE_ERR_INVALID_ARGUMENT;
+    if (!h || !x || !x_trial || intersects(x, x_trial, d)) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects(gtilde, x, d) || intersects(gtilde, x_trial, d)) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects(h, 1, x_trial, d) || intersects(h, 1, gtilde, d)) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(h, 4) || !aligned_to(x, 4) || !aligned_to(x_trial, 4) || !aligned_to(gtilde, 4))
         return CORE_ERR_MISALIGNED;
     return CORE_OK;
@@ -425,7 +443,7 @@ int core_reconstruct_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
 {
     if (!pbar || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4)) return CORE_ERR_MISALIGNED;
-    int rc = validate_update(y, x_new, x_cur, y_next, gtilde);
+    int rc = validate_update(d, y, x_new, x_cur, y_next, gtilde);
     if (rc != CORE_OK) return rc;
     if ((rc = check_device()) != CORE_OK) return rc;
     UpdateArgs up;
@@ -441,7 +459,7 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
     Plan plan;
     int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
     if (rc != CORE_OK) return rc;
-    if ((rc = validate_update(y, x_new, x_cur, y_next, gtilde)) != CORE_OK) return rc;
+    if ((rc = validate_update(d, y, x_new, x_cur, y_next, gtilde)) != CORE_OK) return rc;
     if ((rc = check_device()) != CORE_OK) return rc;
     rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
     if (rc != CORE_OK) return rc;
@@ -476,7 +494,7 @@ int core_reconstruct_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m
 {
     if (!pbar || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4)) return CORE_ERR_MISALIGNED;
-    int rc = validate_trial(h, x, x_trial, gtilde);
+    int rc = validate_trial(d, h, x, x_trial, gtilde);
     if (rc != CORE_OK) return rc;
     if ((rc = check_device()) != CORE_OK) return rc;
     UpdateArgs up;
@@ -493,7 +511,7 @@ int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
     if (rc != CORE_OK) return rc;
     if ((rc = validate_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out)) != CORE_OK) return rc;
-    if ((rc = validate_trial(h_out, x, x_trial, gtilde)) != CORE_OK) return rc;
+    if ((rc = validate_trial(d, h_out, x, x_trial, gtilde)) != CORE_OK) return rc;
     if ((rc = check_device()) != CORE_OK) return rc;
     rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
     if (rc != CORE_OK) return rc;
@@ -509,7 +527,7 @@ int core_accept_trial(uint64_t d, float* f_cur, const float* f_trial, float* x, 
 {
     if (!f_cur || !f_trial || !x || !x_trial || !accepted || d == 0 || d > kMaxD)
         return CORE_ERR_INVALID_ARGUMENT;
-    if (x == x_trial || f_cur == f_trial) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects(x, x_trial, d) || f_cur == f_trial) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(f_cur, 4) || !aligned_to(f_trial, 4) || !aligned_to(x, 4) || !aligned_to(x_trial, 4) ||
         !aligned_to(accepted, 4))
         return CORE_ERR_MISALIGNED;

@@ -149,13 +149,22 @@ def test_nonconvex_entry_points_arguments():
     assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 64, None, None) == E.ERR_INVALID_ARGUMENT
     assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 128, FAKE + 64, None) == E.ERR_INVALID_ARGUMENT
     assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 33, FAKE + 64, FAKE + 128, None, None) == E.ERR_MISALIGNED
+    # overlapping ranges, not just equal pointers (d = 16 floats = 64 bytes)
+    assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 96, None, None) == E.ERR_INVALID_ARGUMENT
+    assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 128, FAKE + 160, None) == E.ERR_INVALID_ARGUMENT
+    assert tr(1, 0, 16, 4, FAKE, 0.25, FAKE + 132, FAKE + 64, FAKE + 128, None, None) == E.ERR_INVALID_ARGUMENT
+    up = L.core_reconstruct_update
+    assert up(1, 0, 16, 4, FAKE, 0.25, 0.1, FAKE + 64, FAKE + 96, None, 0.0, None, None, None) == E.ERR_INVALID_ARGUMENT
+    assert up(1, 0, 16, 4, FAKE, 0.25, 0.1, FAKE + 64, FAKE + 128, None, 0.0, None, FAKE + 100, None) == E.ERR_INVALID_ARGUMENT
+    assert up(1, 0, 16, 4, FAKE, 0.25, 0.1, FAKE + 64, FAKE + 128, FAKE + 256, 0.5, FAKE + 160, None, None) == E.ERR_INVALID_ARGUMENT
     assert tr(1, 0, 0, 4, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 128, None, None) == E.ERR_INVALID_ARGUMENT
     ac = L.core_accept_trial
     assert ac(16, None, FAKE + 4, FAKE + 64, FAKE + 128, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
     assert ac(16, FAKE, FAKE + 4, FAKE + 64, FAKE + 64, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
+    assert ac(16, FAKE, FAKE + 4, FAKE + 64, FAKE + 124, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
     assert ac(16, FAKE, FAKE + 4, FAKE + 64, FAKE + 128, None, None) == E.ERR_INVALID_ARGUMENT
     assert ac(0, FAKE, FAKE + 4, FAKE + 64, FAKE + 128, FAKE + 8, None) == E.ERR_INVALID_ARGUMENT
-    assert ac(16, FAKE, FAKE + 4, FAKE + 66, FAKE + 128, FAKE + 8, None) == E.ERR_MISALIGNED
+    assert ac(16, FAKE, FAKE + 4, FAKE + 62, FAKE + 128, FAKE + 8, None) == E.ERR_MISALIGNED
     wsb = core.core_workspace_bytes(1024, 16, 4)
     rt = L.core_round_trial
     ok_args = [1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE + 4096, 4.0, 1.0, 1.0, FAKE + 8192, FAKE + 8196,
