@@ -33,7 +33,9 @@
  *   - Return value: CORE_OK (0) or a negative CORE_ERR_* code.  Arguments are
  *     validated on the host before anything is launched, so a failing call
  *     enqueues nothing and writes nothing.
- *   - Limits: 1 <= d <= 2^34, 1 <= m <= 2^32-1, 1 <= n <= 65535, ld >= d.
+ *   - Limits: 1 <= d <= 2^34, 1 <= m <= 2^32-1, 1 <= n <= 65535, ld >= d, and
+ *     ceil(d / 2^18) * ceil(m / 256) < 2^31 (one projection block per 2^18 coordinates x 256
+ *     vectors at the largest sizes; d * m below ~1.4e17 always qualifies).
  *     fp32 pointers must be 4-byte aligned, bf16 pointers 2-byte aligned; rows of G
  *     may start at any element.  gtilde is written with 128-bit stores when it is
  *     16-byte aligned and with scalar stores otherwise.
@@ -235,6 +237,16 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
                             void *ws, size_t ws_bytes, core_stream stream);
 
 /* ---- test-only exports: raw generator output -------------------------------- */
+
+/* The launch plan core_compress_batched / core_round would use for these sizes (host arithmetic,
+ * nothing is launched; `plan` is a HOST pointer):
+ *   plan[0] 1 = lanes-over-coordinates projection (few vectors or little work), 0 = lanes-over-vectors
+ *   plan[1] vector tiles (256 vectors each; groups of 4 vectors in mode 1)
+ *   plan[2] chunks of d            plan[3] tiles per chunk (256 coordinates each; 1024 in mode 1)
+ *   plan[4] slices of the cross-chunk sum
+ *   plan[5] projection blocks launched per pass of clients
+ * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */
+int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6]);
 
 /* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks.  out device uint32. */
 int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,

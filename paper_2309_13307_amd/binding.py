@@ -29,7 +29,7 @@ EXPORTS = (
     "core_xi_bytes", "core_compress_batched_store_xi", "core_reconstruct_from_xi",
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
-    "core_accept_trial",
+    "core_accept_trial", "core_debug_plan",
 )
 
 
@@ -92,6 +92,8 @@ def load_library() -> ctypes.CDLL:
     L.core_round_trial.restype = i32
     L.core_accept_trial.argtypes = [u64, vp, vp, vp, vp, vp, vp]
     L.core_accept_trial.restype = i32
+    L.core_debug_plan.argtypes = [u64, u32, u32, ctypes.POINTER(u64)]
+    L.core_debug_plan.restype = i32
     L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     L.core_debug_philox.restype = i32
     L.core_debug_xi.argtypes = [u64, u64, u32, u64, u64, vp, vp]
@@ -306,6 +308,15 @@ def core_accept_trial(f_cur: torch.Tensor, f_trial: torch.Tensor, x: torch.Tenso
     rc = load_library().core_accept_trial(x.numel(), f_cur.data_ptr(), f_trial.data_ptr(), x.data_ptr(),
                                           x_trial.data_ptr(), accepted.data_ptr(), _stream())
     _check(rc, "core_accept_trial")
+
+
+def core_debug_plan(d: int, m: int, n: int) -> dict:
+    """The projection launch plan for these sizes (host arithmetic only)."""
+    out = (ctypes.c_uint64 * 6)()
+    rc = load_library().core_debug_plan(d, m, n, out)
+    _check(rc, "core_debug_plan")
+    keys = ("qmode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks")
+    return dict(zip(keys, (int(v) for v in out)))
 
 
 def core_xi_bytes(d: int, m: int) -> int:

@@ -39,6 +39,7 @@ constexpr uint32_t kQTilesPerChunkMax = 64;   // bounds the fp32 chains of the l
 // combined in fp64.  Capping the tiles per chunk keeps that fp32 chain at the length the accuracy
 // bar was verified for (GPT-2-sized d: 950), whatever d is.
 constexpr uint32_t kTilesPerChunkMax = 1024;
+constexpr uint64_t kMaxGridBlocks = 0x7fffffffull;   // HIP's limit on gridDim.x
 
 // Split d into chunks of whole tiles so that (chunks x vector tiles) is about 8192 equal blocks:
 // four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens out speed differences
@@ -72,6 +73,9 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
         p.tiles_per_chunk = (uint32_t)tpc;
         p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
     }
+    // one block per (chunk, vector tile): the grid must stay a valid launch
+    const uint64_t grid = p.qmode ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
+    if (grid > kMaxGridBlocks) return false;
     uint32_t Z = p.nchunks / 128u;
     if (Z < 1) Z = 1;
     if (Z > 16) Z = 16;
@@ -595,6 +599,19 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
     rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream, xi);
     if (rc != CORE_OK) return rc;
     return enqueue_reconstruct_xi(d, m, pbar, 1.0f / (float)m, xi, gtilde, (hipStream_t)stream);
+}
+
+int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6])
+{
+    Plan p;
+    if (!plan || !make_plan(d, m, n, true, p)) return CORE_ERR_INVALID_ARGUMENT;
+    plan[0] = p.qmode ? 1 : 0;
+    plan[1] = p.jtiles;
+    plan[2] = p.nchunks;
+    plan[3] = p.tiles_per_chunk;
+    plan[4] = p.Z;
+    plan[5] = p.qmode ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
+    return CORE_OK;
 }
 
 int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,

@@ -203,3 +203,46 @@ def test_header_compiles_and_links_from_plain_c(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
     assert "c client ok" in res.stdout
+
+
+def test_launch_plan_invariants():
+    """Host logic of the projection plan, over random sizes: every coordinate and vector is
+    covered exactly once, the fp32 chains stay within their caps, the grid is launchable, the
+    workspace holds the partials, and the plan is a pure function of (d, m, n)."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=400, deadline=None)
+    @given(st.integers(1, 1 << 34), st.integers(1, 1 << 22), st.integers(1, 65535))
+    def check(d, m, n):
+        p = core.core_debug_plan(d, m, n)
+        assert p == core.core_debug_plan(d, m, n)
+        if p["qmode"]:
+            tile, per_j = 1024, 4
+            assert p["tiles_per_chunk"] <= 64
+        else:
+            tile, per_j = 256, 256
+            assert p["tiles_per_chunk"] <= 1024
+        tiles = -(-d // tile)
+        assert (p["nchunks"] - 1) * p["tiles_per_chunk"] < tiles <= p["nchunks"] * p["tiles_per_chunk"]
+        assert (p["jtiles"] - 1) * per_j < m <= p["jtiles"] * per_j
+        assert p["nchunks"] * p["jtiles"] <= p["blocks"] < (1 << 31)
+        assert 1 <= p["slices"] <= 16
+        ws = core.core_workspace_bytes(d, m, n)
+        assert ws >= 4 * p["nchunks"] * n * m + 8 * p["slices"] * n * m
+        assert ws % 256 == 0
+
+    check()
+    # the headline shapes keep the plan the profiles were taken with
+    assert core.core_debug_plan(25_557_032, 1024, 8) == {
+        "qmode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160}
+    p5 = core.core_debug_plan(124_439_808, 4096, 16)
+    assert (p5["qmode"], p5["jtiles"], p5["tiles_per_chunk"]) == (0, 16, 950)
+    assert core.core_debug_plan(1024, 16, 4)["qmode"] == 1
+    # sizes whose grid would not be launchable are refused up front
+    import ctypes
+    out = (ctypes.c_uint64 * 6)()
+    L = core.load_library()
+    assert L.core_debug_plan(1 << 34, (1 << 32) - 1, 1, out) == binding.ERR_INVALID_ARGUMENT
+    assert core.core_workspace_bytes(1 << 34, (1 << 32) - 1, 1) == 0
+    assert L.core_debug_plan(0, 4, 1, out) == binding.ERR_INVALID_ARGUMENT
+    assert L.core_debug_plan(16, 4, 1, None) == binding.ERR_INVALID_ARGUMENT
