@@ -167,3 +167,14 @@ class RobustCoreGD:
         self.f_trial.copy_(self.loss(self.x_trial).reshape(1))
         binding.core_accept_trial(self.f_cur, self.f_trial, self.x, self.x_trial, self.accepted)
         return G
+
+    def round_option2(self, k: int, h: float, gtilde: torch.Tensor | None = None) -> torch.Tensor:
+        """One iteration of Algorithm 3, Option II: the step h is a constant of the run
+        (`binding.core_step_size_option2`), so the trial point comes from the fused update entry
+        point; the comparison step is the same."""
+        G = self.client_gradients(self.x)
+        binding.core_round_update(self.seed, k, G, self.m, h, self.x, self.x_trial, self.pbar, self.ws,
+                                  gtilde=gtilde)
+        self.f_trial.copy_(self.loss(self.x_trial).reshape(1))
+        binding.core_accept_trial(self.f_cur, self.f_trial, self.x, self.x_trial, self.accepted)
+        return G

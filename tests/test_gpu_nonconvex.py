@@ -213,3 +213,45 @@ def test_algorithm3_on_robust_regression():
             assert fs[-1] < 0.9 * fs[0]
         if label == "steps large enough for rejections":
             assert 0 < n_acc < pr.rounds
+
+
+@pytest.mark.timeout(300)
+def test_algorithm3_option2_on_robust_regression():
+    pr = workloads.robust_problem()
+    rows, d = pr.A.shape
+    _say(f"Algorithm 3, Option II on robust regression: d={d} m={pr.m} n={pr.n}")
+    A64, b64 = pr.A.astype(np.float64), pr.b.astype(np.float64)
+    f64 = lambda x: onc.robust_loss(A64, b64, x)
+    grads64 = lambda x: onc.robust_client_gradients(A64, b64, x, pr.n)
+    run = coregd.RobustCoreGD(pr.A, pr.b, pr.n, pr.m, pr.seed)
+    Delta = f64(np.zeros(d))
+    for label, r1, H in (("the paper's constants", run.r1, run.H), ("large steps", run.r1 * 2e-2, run.H * 1e-12)):
+        run = coregd.RobustCoreGD(pr.A, pr.b, pr.n, pr.m, pr.seed)
+        h = core.core_step_size_option2(d, pr.m, r1, H, run.L, Delta)
+        assert math.isclose(h, onc.step_size_option2(d, pr.m, r1, H, run.L, Delta), rel_tol=1e-12)
+        fs = [run.f_cur.item()]
+        rounds = 20
+        for k in range(rounds):
+            x_before = run.x.clone()
+            f_before = run.f_cur.item()
+            G = run.round_option2(k, h)
+            torch.cuda.synchronize()
+            xb = x_before.cpu().numpy().astype(np.float64)
+            _, _, gt_ref = oracle.core_round(pr.seed, k, G.cpu().numpy(), pr.m)
+            xt_gpu = run.x_trial.cpu().numpy().astype(np.float64)
+            step = h * gt_ref
+            assert np.linalg.norm(xt_gpu - (xb - step)) <= 1e-5 * np.linalg.norm(step) + 1.2e-7 * np.linalg.norm(xb)
+            take = onc.comparison_step(f_before, run.f_trial.item())
+            assert run.accepted.item() == int(take)
+            assert torch.equal(run.x, run.x_trial if take else x_before)
+            fs.append(run.f_cur.item())
+        fs = np.array(fs)
+        assert np.all(np.diff(fs) <= 0.0)
+        _say(f"Option II, {label}: h={h:.3e}, f {fs[0]:.6f} -> {fs[-1]:.6f}")
+        # the oracle's own Option II run from the same start: same step, f within fp32 evaluation error
+        ref = onc.core_gd_nonconvex(f64, grads64, np.zeros(d), pr.m, rounds, pr.seed, option=2, r1=r1, H=H,
+                                    L=run.L, Delta=Delta)
+        assert ref["h"][0] == onc.step_size_option2(d, pr.m, r1, H, run.L, Delta)
+        if label == "large steps":
+            assert fs[-1] < 0.95 * fs[0]
+            assert abs(fs[-1] - ref["f"][-1]) <= 2e-3 * ref["f"][0]
