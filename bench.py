@@ -194,6 +194,9 @@ def main():
         "ms_per_step_median": per_round[len(per_round) // 2],
         "ms_per_step_min": per_round[0],
         "pct_fp32_valu_peak": 100.0 * ach_round / PEAK_LANE_OPS,
+        # for context: the same work counted in flops (an FMA as 2, every other lane-op as 1)
+        # against the published 157.3 TFLOP/s, which only packed-fp32 FMAs can reach
+        "flop_equivalent_TFLOPs": pairs * (52 + 2 * (n + 1)) / (ms_per_step * 1e-3) / 1e12,
         "roofline": {
             "bound": "alu",
             "kernel": "project_kernel (core_compress_batched: projection + cross-chunk sum)",

@@ -67,8 +67,8 @@ def test_config4_full_size_sampled():
     torch.cuda.synchronize()
     assert torch.equal(pbar, pbar2) and torch.equal(gtilde, gtilde2)
     assert bool(torch.isfinite(gtilde).all())
-    jidx = np.array([0, 1, 255, 256, 511, 777, 1000, 1023], dtype=np.uint32)
-    _sampled_check(case, 0, pbar, gtilde, jidx, 2048, "config4")
+    jidx = np.array([0, 1, 63, 64, 255, 256, 257, 511, 512, 640, 777, 800, 999, 1000, 1022, 1023], dtype=np.uint32)
+    _sampled_check(case, 0, pbar, gtilde, jidx, 4096, "config4")
     # |gtilde|^2 ~ (d/m) |mean g|^2 when d >> m (second-moment identity of the estimator): a
     # whole-output sanity check that costs nothing
     gbar = case.G.float().mean(dim=0)
