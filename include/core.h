@@ -148,6 +148,25 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
                       float *gtilde,
                       void *ws, size_t ws_bytes, core_stream stream);
 
+/* ---- round counter in device memory (for replayed launch sequences) --------------------------
+ * Algorithms 1 and 2 draw fresh Gaussian vectors every round, so the round counter must change
+ * from one round to the next.  A caller that records one iteration into a HIP graph and replays it
+ * cannot change a by-value argument between replays; core_round_update_r is core_round_update
+ * with the counter read from device memory when the kernels run:
+ *   round = *round_dev      (device uint64, 8-byte aligned; every kernel of the call reads it, so it
+ *                            must not change while the call's kernels are in flight)
+ * core_advance_round enqueues *round_dev += 1 on `stream`; put it after the round in the recorded
+ * sequence.  Neither call uses a memset node, so both may be captured. */
+int core_round_update_r(uint64_t seed, const uint64_t *round_dev, uint64_t d, uint32_t m, uint32_t n,
+                        const void *G, core_dtype dt, uint64_t ld,
+                        float *pbar, float h,
+                        const float *y, float *x_new,
+                        const float *x_cur, float one_minus_beta, float *y_next,
+                        float *gtilde,
+                        void *ws, size_t ws_bytes, core_stream stream);
+
+int core_advance_round(uint64_t *round_dev, core_stream stream);
+
 /* ---- CORE-GD for non-convex objectives (Algorithm 3, Section 5) -----------------------------
  * An iteration of Algorithm 3 is a round of Algorithm 2 plus three things: a scalar p formed from
  * the combined projections, a step size h_k chosen from p (Option I) or from constants

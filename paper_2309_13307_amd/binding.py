@@ -29,7 +29,7 @@ EXPORTS = (
     "core_xi_bytes", "core_compress_batched_store_xi", "core_reconstruct_from_xi",
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
-    "core_accept_trial", "core_debug_plan",
+    "core_accept_trial", "core_debug_plan", "core_round_update_r", "core_advance_round",
 )
 
 
@@ -92,6 +92,11 @@ def load_library() -> ctypes.CDLL:
     L.core_round_trial.restype = i32
     L.core_accept_trial.argtypes = [u64, vp, vp, vp, vp, vp, vp]
     L.core_accept_trial.restype = i32
+    L.core_round_update_r.argtypes = [u64, vp, u64, u32, u32, vp, i32, u64, vp, f32, vp, vp, vp, f32, vp, vp,
+                                      vp, sz, vp]
+    L.core_round_update_r.restype = i32
+    L.core_advance_round.argtypes = [vp, vp]
+    L.core_advance_round.restype = i32
     L.core_debug_plan.argtypes = [u64, u32, u32, ctypes.POINTER(u64)]
     L.core_debug_plan.restype = i32
     L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
@@ -308,6 +313,36 @@ def core_accept_trial(f_cur: torch.Tensor, f_trial: torch.Tensor, x: torch.Tenso
     rc = load_library().core_accept_trial(x.numel(), f_cur.data_ptr(), f_trial.data_ptr(), x.data_ptr(),
                                           x_trial.data_ptr(), accepted.data_ptr(), _stream())
     _check(rc, "core_accept_trial")
+
+
+def core_round_update_r(seed: int, round_dev: torch.Tensor, G: torch.Tensor, m: int, h: float, y: torch.Tensor,
+                        x_new: torch.Tensor, pbar: torch.Tensor, ws: torch.Tensor,
+                        x_cur: torch.Tensor | None = None, one_minus_beta: float = 0.0,
+                        y_next: torch.Tensor | None = None, gtilde: torch.Tensor | None = None,
+                        d: int | None = None) -> None:
+    """core_round_update with the round counter read from the device tensor `round_dev` (int64, one
+    element) when the kernels run; for iterations recorded into a HIP graph."""
+    _require_cuda(round_dev, G, y, x_new, pbar, ws, x_cur, y_next, gtilde)
+    if round_dev.dtype != torch.int64 or round_dev.numel() != 1:
+        raise TypeError("round_dev must be a one-element int64 tensor")
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    rc = load_library().core_round_update_r(seed, round_dev.data_ptr(), d, m, n, G.data_ptr(), _dtype_code(G),
+                                            ld, pbar.data_ptr(), h, y.data_ptr(), x_new.data_ptr(),
+                                            _ptr(x_cur), one_minus_beta, _ptr(y_next), _ptr(gtilde),
+                                            ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "core_round_update_r")
+
+
+def core_advance_round(round_dev: torch.Tensor) -> None:
+    """Enqueue round_dev += 1 on the current stream."""
+    _require_cuda(round_dev)
+    if round_dev.dtype != torch.int64 or round_dev.numel() != 1:
+        raise TypeError("round_dev must be a one-element int64 tensor")
+    _check(load_library().core_advance_round(round_dev.data_ptr(), _stream()), "core_advance_round")
 
 
 def core_debug_plan(d: int, m: int, n: int) -> dict:

@@ -64,6 +64,27 @@ class RidgeCoreGD:
             self.x -= h * self.gtilde
         return G
 
+    def capture_round(self, h: float, first_round: int = 0) -> "torch.cuda.CUDAGraph":
+        """Record one iteration of Algorithm 2 (client gradients, the fused round, the round counter
+        advancing on the device) into a HIP graph; every replay is the next round.  The iteration is
+        launch-bound at this size, which is what the graph removes."""
+        self.round_dev = torch.full((1,), first_round, dtype=torch.int64, device=self.x.device)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):            # library handles and workspaces are created outside capture
+            for _ in range(2):
+                self.client_gradients()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            G = self.client_gradients()
+            binding.core_round_update_r(self.seed, self.round_dev, G, self.m, h, self.x, self.x, self.pbar,
+                                        self.ws, gtilde=self.gtilde)
+            binding.core_advance_round(self.round_dev)
+        self._graph_G = G                        # keeps the captured buffer alive
+        return graph
+
     def agd_round(self, k: int, h: float, beta: float) -> None:
         """One round of CORE-AGD (heavy-ball form).  State: self.x = x^k, self.y = y^k (the
         extrapolated point; equal to x^0 before the first round).  The kernel epilogue writes

@@ -182,7 +182,8 @@ int validate_reconstruct(uint64_t d, uint32_t m, const float* pbar, const float*
 
 int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
                      const void* G, core_dtype dt, uint64_t ld, float* P, float* pbar,
-                     void* ws, const Plan& plan, hipStream_t st, float* xi_store = nullptr)
+                     void* ws, const Plan& plan, hipStream_t st, float* xi_store = nullptr,
+                     const uint64_t* round_dev = nullptr)
 {
     char* base = (char*)ws;
     float* part = (float*)(base + plan.part_off);
@@ -192,6 +193,7 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     a.G = G; a.ld = ld; a.d = d; a.m = m; a.n = n;
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
     a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
+    a.round_dev = reinterpret_cast<const uint32_t*>(round_dev);   // little-endian: lo word first
     a.jtiles = plan.jtiles; a.nchunks = plan.nchunks; a.tiles_per_chunk = plan.tiles_per_chunk;
     a.part = part;
     a.xi_store = xi_store;
@@ -259,6 +261,7 @@ struct UpdateArgs {
     float* y_next = nullptr;
     float h = 0.0f, omb = 0.0f;
     const float* h_dev = nullptr;
+    const uint64_t* round_dev = nullptr;
 };
 
 int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, const float* pbar,
@@ -271,6 +274,7 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     bool vec = !gtilde || aligned_to(gtilde, 16);
     a.y = nullptr; a.x_new = nullptr; a.x_cur = nullptr; a.y_next = nullptr; a.h = 0.0f; a.omb = 0.0f;
     a.h_dev = nullptr;
+    a.round_dev = up ? reinterpret_cast<const uint32_t*>(up->round_dev) : nullptr;
     if (up) {
         a.y = up->y; a.x_new = up->x_new; a.x_cur = up->x_cur; a.y_next = up->y_next;
         a.h = up->h; a.omb = up->omb; a.h_dev = up->h_dev;
@@ -470,6 +474,39 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
     UpdateArgs up;
     up.y = y; up.x_new = x_new; up.x_cur = x_cur; up.y_next = y_next; up.h = h; up.omb = one_minus_beta;
     return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_round_update_r(uint64_t seed, const uint64_t* round_dev, uint64_t d, uint32_t m, uint32_t n,
+                        const void* G, core_dtype dt, uint64_t ld, float* pbar, float h, const float* y,
+                        float* x_new, const float* x_cur, float one_minus_beta, float* y_next, float* gtilde,
+                        void* ws, size_t ws_bytes, core_stream stream)
+{
+    if (!round_dev) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(round_dev, 8)) return CORE_ERR_MISALIGNED;
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = validate_update(d, y, x_new, x_cur, y_next, gtilde)) != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    rc = enqueue_compress(seed, 0, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream, nullptr,
+                          round_dev);
+    if (rc != CORE_OK) return rc;
+    UpdateArgs up;
+    up.y = y; up.x_new = x_new; up.x_cur = x_cur; up.y_next = y_next; up.h = h; up.omb = one_minus_beta;
+    up.round_dev = round_dev;
+    return enqueue_reconstruct(seed, 0, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_advance_round(uint64_t* round_dev, core_stream stream)
+{
+    if (!round_dev) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(round_dev, 8)) return CORE_ERR_MISALIGNED;
+    int rc = check_device();
+    if (rc != CORE_OK) return rc;
+    hipLaunchKernelGGL(advance_round_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, round_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return CORE_OK;
 }
 
 int core_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, double r1, double H,

@@ -38,6 +38,7 @@ struct ProjectArgs {
     uint32_t nc;          // clients in this pass (<= NC)
     uint32_t k0, k1;      // seed halves
     uint32_t r0, r1;      // round halves
+    const uint32_t* round_dev;   // when non-null, the round counter (lo, hi) is read from here instead
     uint32_t jtiles;      // ceil(m / kThreads)
     uint32_t nchunks;     // chunks of d
     uint32_t tiles_per_chunk;
@@ -83,7 +84,7 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
 
     // lanes differ in j (counter word 1) only: the state is fully divergent after 3 rounds
     Generator<3, 4> gen;
-    gen.init(a.k0, a.k1, a.r0, a.r1);
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
 
     float acc_outer[NC];
 #pragma unroll
@@ -180,7 +181,7 @@ __global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
     if (tile_end > tiles_total) tile_end = tiles_total;
 
     Generator<3, 4> gen;
-    gen.init(a.k0, a.k1, a.r0, a.r1);
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
 
     mfma_f32x4 outer[NG];
 #pragma unroll
@@ -274,7 +275,7 @@ __global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
     if (tile_end > tiles_total) tile_end = tiles_total;
 
     Generator<2, 3> gen;
-    gen.init(a.k0, a.k1, a.r0, a.r1);
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
 
     float acc[kQJ][NC];
 #pragma unroll
@@ -410,6 +411,7 @@ struct ReconArgs {
     uint32_t m;
     float scale;
     uint32_t k0, k1, r0, r1;
+    const uint32_t* round_dev;   // when non-null, the round counter (lo, hi) is read from here instead
     int vec_store;        // every output (and y, x_cur) is 16-byte aligned
     // fused optimiser step (UPDATE variant only)
     const float* y;       // [d] point the gradients were taken at
@@ -435,7 +437,7 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
 
     // lanes differ in q (counter word 0) only: the state is fully divergent after 2-3 rounds
     Generator<2, 3> gen;
-    gen.init(a.k0, a.k1, a.r0, a.r1);
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
 
     float outer[kReconBlocks][4];
 #pragma unroll
@@ -593,6 +595,12 @@ __global__ void __launch_bounds__(kThreads) accept_copy_kernel(const int32_t* ac
         const uint64_t i = 4 * t;
         for (uint64_t k = i; k < i + 4 && k < d; ++k) x[k] = x_trial[k];
     }
+}
+
+// Device-resident round counter for replayed launch sequences (HIP graphs): one thread adds 1.
+__global__ void advance_round_kernel(uint64_t* round_dev)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *round_dev += 1;
 }
 
 // Materialised-Xi comparison variant of the reconstruction: gtilde[4q+k] = scale * sum_j pbar[j] *

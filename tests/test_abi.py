@@ -205,6 +205,28 @@ def test_header_compiles_and_links_from_plain_c(tmp_path):
     assert "c client ok" in res.stdout
 
 
+def test_device_round_counter_arguments():
+    L = core.load_library()
+    E = binding
+    wsb = core.core_workspace_bytes(1024, 16, 4)
+    f = L.core_round_update_r
+    ok = [1, FAKE + 8, 1024, 16, 4, FAKE + 0x100000, 0, 1024, FAKE + 4096, 0.1, FAKE + 16384, FAKE + 16384, None, 0.0,
+          None, None, FAKE + 65536, wsb, None]
+    bad = list(ok); bad[1] = None
+    assert f(*bad) == E.ERR_INVALID_ARGUMENT
+    bad = list(ok); bad[1] = FAKE + 4
+    assert f(*bad) == E.ERR_MISALIGNED
+    bad = list(ok); bad[5] = None
+    assert f(*bad) == E.ERR_INVALID_ARGUMENT
+    bad = list(ok); bad[17] = wsb - 1
+    assert f(*bad) == E.ERR_WORKSPACE_TOO_SMALL
+    assert L.core_advance_round(None, None) == E.ERR_INVALID_ARGUMENT
+    assert L.core_advance_round(FAKE + 4, None) == E.ERR_MISALIGNED
+    if not torch.cuda.is_available():
+        assert f(*ok) == E.ERR_NO_DEVICE
+        assert L.core_advance_round(FAKE + 8, None) == E.ERR_NO_DEVICE
+
+
 def test_launch_plan_invariants():
     """Host logic of the projection plan, over random sizes: every coordinate and vector is
     covered exactly once, the fp32 chains stay within their caps, the grid is launchable, the

@@ -7,6 +7,7 @@ start; the loss gap to the closed-form minimiser x* = (A^T A + lam I)^-1 A^T b s
 as fast as the bound that follows from the proof of Theorem 4.2 for the step used, within
 Monte-Carlo slack (one trajectory)."""
 import sys
+import time
 
 import numpy as np
 import pytest
@@ -121,3 +122,60 @@ def test_decentralized_core_gd_small():
     assert np.linalg.norm(X - X_ref) <= 1e-4 * np.linalg.norm(X_ref)
     assert np.abs(X_ref - X_ref.mean(axis=0)).max() > 1e-6     # the copies really differ
     assert losses[-1] < losses[0]
+
+
+@pytest.mark.timeout(300)
+def test_graph_replayed_core_gd_matches_eager():
+    """One iteration of Algorithm 2 recorded into a HIP graph with the round counter in device
+    memory: every replay must be the next round, bit-identical to the eager loop that passes the
+    counter by value, also with eager work and synchronisation between replays."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    pr = workloads.ridge_problem(rows=2048, d=1024, n=8, m=64, rounds=60)
+    d = pr.A.shape[1]
+    s = 1.0 / np.arange(1, d + 1)
+    h = coregd.step_size(s, pr.lam, pr.m)
+    first = (1 << 32) - 20                       # the counter crosses 2^32 during the run
+    _say(f"graph-replayed CORE-GD: d={d} m={pr.m} n={pr.n}, {pr.rounds} rounds from round {first}")
+    eager = coregd.RidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed)
+    xs = []
+    for k in range(pr.rounds):
+        eager.round(first + k, h)
+        xs.append(eager.x.clone())
+    torch.cuda.synchronize()
+
+    run = coregd.RidgeCoreGD(pr.A, pr.b, pr.lam, pr.n, pr.m, pr.seed)
+    graph = run.capture_round(h, first_round=first)
+    torch.cuda.synchronize()
+    assert run.round_dev.item() == first and float(run.x.abs().max()) == 0.0, "capture must not execute"
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for k in range(pr.rounds):
+        graph.replay()
+        if k % 7 == 3:                           # eager work and a sync between replays
+            scratch.add_(1.0)
+            torch.cuda.synchronize()
+        if k % 5 == 0 or k == pr.rounds - 1:
+            torch.cuda.synchronize()
+            assert torch.equal(run.x, xs[k]), f"replay {k} differs from eager round {first + k}"
+    torch.cuda.synchronize()
+    assert run.round_dev.item() == first + pr.rounds
+    # the last round against the oracle, from the gradients the graph used
+    G_host = run._graph_G.cpu().numpy()
+    _, pbar_ref, gt_ref = oracle.core_round(pr.seed, first + pr.rounds - 1, G_host, pr.m)
+    parity.check_gtilde(run.gtilde.cpu().numpy(), gt_ref, "last replayed round")
+
+    # launch overhead: time 200 more rounds each way
+    t = []
+    for mode in ("eager", "graph"):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(200):
+            if mode == "eager":
+                eager.round(first + pr.rounds + k, h)
+            else:
+                graph.replay()
+        torch.cuda.synchronize()
+        t.append((time.perf_counter() - t0) / 200 * 1e6)
+    _say(f"per round: eager {t[0]:.1f} us, graph replay {t[1]:.1f} us")
+    assert torch.equal(run.x, eager.x)
+    assert t[1] < 1.5 * t[0]
