@@ -153,6 +153,28 @@ def test_loop_guarantees_and_a_round_replayed_by_hand():
     np.testing.assert_allclose(out["x"], xt if f(xt) < f(x0) else x0, rtol=1e-12, atol=1e-15)
 
 
+def test_ties_keep_the_current_point_and_every_round_draws_fresh_vectors():
+    assert nc.comparison_step(1.0, 1.0) is False
+    assert nc.comparison_step(1.0, float("nan")) is False and nc.comparison_step(float("nan"), 0.0) is False
+    assert nc.comparison_step(1.0, np.nextafter(1.0, 0.0)) is True
+    A, b, n = _robust_problem()
+    d = A.shape[1]
+    grads = lambda x: nc.robust_client_gradients(A, b, x, n)
+    x0 = np.full(d, 0.25)
+    # a constant objective: the trial point never strictly improves, so x never moves
+    out = nc.core_gd_nonconvex(lambda x: 1.0, grads, x0, 4, 6, 9, option=2, r1=0.5, H=1e-9, L=1.0, Delta=1.0)
+    assert not any(out["accepted"]) and np.array_equal(out["x"], x0)
+    # with x fixed the gradients are fixed, so p changes from round to round only through the
+    # fresh vectors: round k must use counter first_round + k
+    m, c, first = 4, 2.0, 17
+    assert len(set(out["p"])) == len(out["p"])
+    G = grads(x0)
+    out = nc.core_gd_nonconvex(lambda x: 1.0, grads, x0, m, 3, 9, option=1, r1=0.5, H=1e-9, c=c, first_round=first)
+    for k in range(3):
+        pbar = np.array([np.mean([G[i] @ oracle.xi_range(9, first + k, j, 0, d) for i in range(n)]) for j in range(m)])
+        assert math.isclose(out["p"][k], c * math.sqrt(float(np.mean(pbar ** 2))), rel_tol=1e-12)
+
+
 def test_both_branches_of_the_comparison_step_occur():
     A, b, n = _robust_problem()
     d = A.shape[1]
