@@ -125,6 +125,12 @@ def test_core_agd_is_heavy_ball_with_the_estimated_gradient():
     _, _, gt1 = core_round(11, 1, G1, 8)
     x2, _ = coregd.core_agd(A, b, lam, n, 8, 0.1, 0.3, 2, seed=11, x0=x0)
     np.testing.assert_allclose(x2, y1 - 0.1 * gt1, rtol=1e-13, atol=1e-13)
+    # third step: the momentum term is built from the two last iterates x2, x1 (not from y1)
+    y2 = x2 + 0.7 * (x2 - x1)
+    G2 = coregd.client_gradients(A, b, lam, y2, n)
+    _, _, gt2 = core_round(11, 2, G2, 8)
+    x3, _ = coregd.core_agd(A, b, lam, n, 8, 0.1, 0.3, 3, seed=11, x0=x0)
+    np.testing.assert_allclose(x3, y2 - 0.1 * gt2, rtol=1e-13, atol=1e-13)
 
 
 def test_decentralized_core_gd_reduces_to_the_centralized_one():
@@ -147,3 +153,18 @@ def test_decentralized_core_gd_reduces_to_the_centralized_one():
     X2, losses2 = coregd.decentralized_core_gd(A, b, lam, n, m, h, 30, 9, W, gossip_steps=2)
     assert np.abs(X2 - X2.mean(axis=0)).max() > 1e-6
     assert losses2[-1] < losses2[0]
+    # two rounds with a single gossip step, replayed by hand: after round 0 the copies differ, and
+    # in round 1 machine c must take its own gradient at its own copy
+    from oracle import compress, reconstruct
+    rows = A.shape[0] // n
+    X1, _ = coregd.decentralized_core_gd(A, b, lam, n, m, h, 2, 9, W, gossip_steps=1)
+    Xh = np.zeros((n, d))
+    for k in range(2):
+        G = np.stack([n * (A[c * rows:(c + 1) * rows].T @ (A[c * rows:(c + 1) * rows] @ Xh[c]
+                                                         - b[c * rows:(c + 1) * rows])) + lam * Xh[c]
+                      for c in range(n)])
+        P = W @ compress(9, k, G, m)
+        Xh = np.stack([Xh[c] - h * reconstruct(9, k, P[c], n / m, 0, d) / n for c in range(n)])
+        if k == 0:
+            assert np.abs(Xh - Xh.mean(axis=0)).max() > 1e-9
+    np.testing.assert_allclose(X1, Xh, rtol=1e-12, atol=1e-14)
