@@ -394,3 +394,38 @@ def test_extreme_aspect_ratios(d, m, n, variant):
     rng = np.random.default_rng(d + m + n)
     G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
     _run_and_check(404, 7, G, m, what=f"aspect d={d} m={m} n={n}")
+
+
+@pytest.mark.parametrize("scale", [1e30, 1e-30, 1e-38])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_value_ranges(scale, dtype, variant):
+    """Very large and very small gradient entries (down to the edge of the normal range, where
+    some entries and many partial sums are subnormal): fp32 arithmetic must neither overflow nor
+    flush to zero; the usual bars hold because they are relative to |g|."""
+    d, m, n = 3001, 70, 3
+    _say(f"value range scale={scale} {dtype} variant={variant}")
+    rng = np.random.default_rng(17)
+    G32 = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+    G = torch.from_numpy(G32).to(DEV).to(dtype)
+    assert float(G.float().abs().max()) > 0.0
+    _run_and_check(77, 3, G, m, what=f"scale {scale} {dtype}")
+
+
+def test_subnormal_gradients_are_not_flushed(variant):
+    """Every entry subnormal (|g| ~ 1.6e-40): sums carry only the ~16 bits a subnormal of that size
+    has, so the usual bars cannot hold, but a flush to zero anywhere (inputs, products or sums)
+    would leave an error of order one.  Require 1e-3 of |g|."""
+    d, m, n = 3001, 70, 3
+    _say(f"subnormal gradients variant={variant}")
+    rng = np.random.default_rng(18)
+    G32 = (rng.standard_normal((n, d)) * 3e-42).astype(np.float32)
+    G = torch.from_numpy(G32).to(DEV)
+    norms = parity.row_norms(G32)
+    assert norms.min() > 0.0
+    P_ref, pbar_ref, gt_ref = oracle.core_round(5, 1, G32, m)
+    P, pbar = core.core_compress_batched(5, 1, G, m)
+    _, gt = core.core_round(5, 1, G, m)
+    _sync()
+    err = np.abs(P.cpu().numpy().astype(np.float64) - P_ref) / norms[:, None]
+    assert err.max() < 1e-3, f"normalised projection error {err.max():.3e}"
+    assert parity.rel_l2(gt.cpu().numpy(), gt_ref) < 1e-3
