@@ -42,6 +42,8 @@
  *   - Arithmetic: fp32 throughout on the device; per-(client, vector) sums are
  *     blocked (256-coordinate inner sums, then per-chunk sums, then an fp64 sum
  *     over chunks) so that rounding error stays near fp32 epsilon at any d.
+ *     Subnormal inputs, products and sums are kept (no flush to zero); a projection is
+ *     finite as long as |<g, xi_j>| fits fp32; non-finite inputs give non-finite outputs.
  */
 #ifndef CORE_H_
 #define CORE_H_
