@@ -429,3 +429,50 @@ def test_subnormal_gradients_are_not_flushed(variant):
     err = np.abs(P.cpu().numpy().astype(np.float64) - P_ref) / norms[:, None]
     assert err.max() < 1e-3, f"normalised projection error {err.max():.3e}"
     assert parity.rel_l2(gt.cpu().numpy(), gt_ref) < 1e-3
+
+
+def test_host_threads_with_their_own_streams():
+    """The library keeps no shared mutable state: host threads that call it at the same time, each
+    on its own stream with its own scratch and outputs, get the single-thread results bit for bit."""
+    import threading
+    rng = np.random.default_rng(78)
+    d, m, n, nthreads, rounds = 20000, 200, 4, 4, 8
+    _say(f"host threads d={d} m={m} n={n} threads={nthreads}")
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
+    ws0 = core.alloc_workspace(d, m, n)
+    refs = []
+    for r in range(rounds):
+        pb, gt = core.core_round(9, r, G, m, ws=ws0)
+        refs.append((pb.clone(), gt.clone()))
+    _sync()
+    results = [None] * nthreads
+    errors = []
+
+    def worker(t):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            ws = core.alloc_workspace(d, m, n)
+            outs = []
+            with torch.cuda.stream(stream):
+                for r in range(rounds):
+                    pb = torch.empty(m, device=DEV)
+                    gt = torch.empty(d, device=DEV)
+                    core.core_round(9, r, G, m, pbar=pb, gtilde=gt, ws=ws)
+                    outs.append((pb, gt))
+            stream.synchronize()
+            results[t] = outs
+        except Exception as exc:   # surfaced in the main thread below
+            errors.append(exc)
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(nthreads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+        assert not th.is_alive(), "worker did not finish"
+    assert not errors, errors
+    _sync()
+    for t in range(nthreads):
+        for r in range(rounds):
+            assert torch.equal(results[t][r][0], refs[r][0]) and torch.equal(results[t][r][1], refs[r][1]), (t, r)
