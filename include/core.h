@@ -169,6 +169,13 @@ int core_round_update_r(uint64_t seed, const uint64_t *round_dev, uint64_t d, ui
 
 int core_advance_round(uint64_t *round_dev, core_stream stream);
 
+/* core_round_trial (Algorithm 3, below) with the counter read from device memory, for the same use. */
+int core_round_trial_r(uint64_t seed, const uint64_t *round_dev, uint64_t d, uint32_t m, uint32_t n,
+                       const void *G, core_dtype dt, uint64_t ld,
+                       float *pbar, float c, double r1, double H, float *p_out, float *h_out,
+                       const float *x, float *x_trial, float *gtilde,
+                       void *ws, size_t ws_bytes, core_stream stream);
+
 /* ---- CORE-GD for non-convex objectives (Algorithm 3, Section 5) -----------------------------
  * An iteration of Algorithm 3 is a round of Algorithm 2 plus three things: a scalar p formed from
  * the combined projections, a step size h_k chosen from p (Option I) or from constants

@@ -30,6 +30,7 @@ EXPORTS = (
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
     "core_accept_trial", "core_debug_plan", "core_round_update_r", "core_advance_round",
+    "core_round_trial_r",
 )
 
 
@@ -95,6 +96,9 @@ def load_library() -> ctypes.CDLL:
     L.core_round_update_r.argtypes = [u64, vp, u64, u32, u32, vp, i32, u64, vp, f32, vp, vp, vp, f32, vp, vp,
                                       vp, sz, vp]
     L.core_round_update_r.restype = i32
+    L.core_round_trial_r.argtypes = [u64, vp, u64, u32, u32, vp, i32, u64, vp, f32, f64, f64, vp, vp, vp, vp,
+                                     vp, vp, sz, vp]
+    L.core_round_trial_r.restype = i32
     L.core_advance_round.argtypes = [vp, vp]
     L.core_advance_round.restype = i32
     L.core_debug_plan.argtypes = [u64, u32, u32, ctypes.POINTER(u64)]
@@ -335,6 +339,26 @@ def core_round_update_r(seed: int, round_dev: torch.Tensor, G: torch.Tensor, m: 
                                             _ptr(x_cur), one_minus_beta, _ptr(y_next), _ptr(gtilde),
                                             ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "core_round_update_r")
+
+
+def core_round_trial_r(seed: int, round_dev: torch.Tensor, G: torch.Tensor, m: int, c: float, r1: float,
+                       H: float, x: torch.Tensor, x_trial: torch.Tensor, pbar: torch.Tensor,
+                       p_out: torch.Tensor | None, h_out: torch.Tensor, ws: torch.Tensor,
+                       gtilde: torch.Tensor | None = None, d: int | None = None) -> None:
+    """core_round_trial with the round counter read from the device tensor `round_dev`."""
+    _require_cuda(round_dev, G, x, x_trial, pbar, p_out, h_out, ws, gtilde)
+    if round_dev.dtype != torch.int64 or round_dev.numel() != 1:
+        raise TypeError("round_dev must be a one-element int64 tensor")
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    rc = load_library().core_round_trial_r(seed, round_dev.data_ptr(), d, m, n, G.data_ptr(), _dtype_code(G), ld,
+                                           pbar.data_ptr(), c, r1, H, _ptr(p_out), h_out.data_ptr(),
+                                           x.data_ptr(), x_trial.data_ptr(), _ptr(gtilde), ws.data_ptr(),
+                                           ws.numel(), _stream())
+    _check(rc, "core_round_trial_r")
 
 
 def core_advance_round(round_dev: torch.Tensor) -> None:

@@ -199,3 +199,30 @@ class RobustCoreGD:
         self.f_trial.copy_(self.loss(self.x_trial).reshape(1))
         binding.core_accept_trial(self.f_cur, self.f_trial, self.x, self.x_trial, self.accepted)
         return G
+
+    def capture_round(self, r1: float | None = None, H: float | None = None,
+                      first_round: int = 0) -> "torch.cuda.CUDAGraph":
+        """Record one whole iteration of Algorithm 3, Option I (client gradients, round, statistic,
+        step, trial point, f at the trial point, comparison step, counter advance) into a HIP
+        graph.  Nothing in the iteration reads device memory from the host, so a replay is the
+        next iteration, accept or reject included."""
+        self.round_dev = torch.full((1,), first_round, dtype=torch.int64, device=self.x.device)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):            # library handles and workspaces are created outside capture
+            for _ in range(2):
+                self.client_gradients(self.x)
+                self.loss(self.x)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            G = self.client_gradients(self.x)
+            binding.core_round_trial_r(self.seed, self.round_dev, G, self.m, self.c,
+                                       self.r1 if r1 is None else r1, self.H if H is None else H,
+                                       self.x, self.x_trial, self.pbar, self.p, self.h, self.ws)
+            self.f_trial.copy_(self.loss(self.x_trial).reshape(1))
+            binding.core_accept_trial(self.f_cur, self.f_trial, self.x, self.x_trial, self.accepted)
+            binding.core_advance_round(self.round_dev)
+        self._graph_G = G
+        return graph

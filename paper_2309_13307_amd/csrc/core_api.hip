@@ -543,10 +543,10 @@ int core_reconstruct_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m
     return enqueue_reconstruct(seed, round, d, m, pbar, scale, gtilde, (hipStream_t)stream, &up);
 }
 
-int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n, const void* G,
-                     core_dtype dt, uint64_t ld, float* pbar, float c, double r1, double H, float* p_out,
-                     float* h_out, const float* x, float* x_trial, float* gtilde, void* ws, size_t ws_bytes,
-                     core_stream stream)
+static int round_trial_impl(uint64_t seed, uint64_t round, const uint64_t* round_dev, uint64_t d, uint32_t m,
+                            uint32_t n, const void* G, core_dtype dt, uint64_t ld, float* pbar, float c, double r1,
+                            double H, float* p_out, float* h_out, const float* x, float* x_trial, float* gtilde,
+                            void* ws, size_t ws_bytes, core_stream stream)
 {
     Plan plan;
     int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, ws, ws_bytes, plan);
@@ -554,13 +554,34 @@ int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     if ((rc = validate_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out)) != CORE_OK) return rc;
     if ((rc = validate_trial(d, h_out, x, x_trial, gtilde)) != CORE_OK) return rc;
     if ((rc = check_device()) != CORE_OK) return rc;
-    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
+    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream, nullptr,
+                          round_dev);
     if (rc != CORE_OK) return rc;
     if ((rc = enqueue_nonconvex_step(d, m, pbar, c, r1, H, p_out, h_out, (hipStream_t)stream)) != CORE_OK)
         return rc;
     UpdateArgs up;
-    up.y = x; up.x_new = x_trial; up.h_dev = h_out;
+    up.y = x; up.x_new = x_trial; up.h_dev = h_out; up.round_dev = round_dev;
     return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream, &up);
+}
+
+int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n, const void* G,
+                     core_dtype dt, uint64_t ld, float* pbar, float c, double r1, double H, float* p_out,
+                     float* h_out, const float* x, float* x_trial, float* gtilde, void* ws, size_t ws_bytes,
+                     core_stream stream)
+{
+    return round_trial_impl(seed, round, nullptr, d, m, n, G, dt, ld, pbar, c, r1, H, p_out, h_out, x, x_trial,
+                            gtilde, ws, ws_bytes, stream);
+}
+
+int core_round_trial_r(uint64_t seed, const uint64_t* round_dev, uint64_t d, uint32_t m, uint32_t n, const void* G,
+                       core_dtype dt, uint64_t ld, float* pbar, float c, double r1, double H, float* p_out,
+                       float* h_out, const float* x, float* x_trial, float* gtilde, void* ws, size_t ws_bytes,
+                       core_stream stream)
+{
+    if (!round_dev) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(round_dev, 8)) return CORE_ERR_MISALIGNED;
+    return round_trial_impl(seed, 0, round_dev, d, m, n, G, dt, ld, pbar, c, r1, H, p_out, h_out, x, x_trial,
+                            gtilde, ws, ws_bytes, stream);
 }
 
 int core_accept_trial(uint64_t d, float* f_cur, const float* f_trial, float* x, const float* x_trial,

@@ -220,6 +220,15 @@ def test_device_round_counter_arguments():
     assert f(*bad) == E.ERR_INVALID_ARGUMENT
     bad = list(ok); bad[17] = wsb - 1
     assert f(*bad) == E.ERR_WORKSPACE_TOO_SMALL
+    g = L.core_round_trial_r
+    okt = [1, FAKE + 8, 1024, 16, 4, FAKE + 0x100000, 0, 1024, FAKE + 4096, 4.0, 1.0, 1.0, FAKE + 8192, FAKE + 8196,
+           FAKE + 16384, FAKE + 32768, None, FAKE + 65536, wsb, None]
+    bad = list(okt); bad[1] = None
+    assert g(*bad) == E.ERR_INVALID_ARGUMENT
+    bad = list(okt); bad[1] = FAKE + 12
+    assert g(*bad) == E.ERR_MISALIGNED
+    bad = list(okt); bad[15] = bad[14]
+    assert g(*bad) == E.ERR_INVALID_ARGUMENT
     assert L.core_advance_round(None, None) == E.ERR_INVALID_ARGUMENT
     assert L.core_advance_round(FAKE + 4, None) == E.ERR_MISALIGNED
     if not torch.cuda.is_available():

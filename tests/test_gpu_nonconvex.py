@@ -255,3 +255,40 @@ def test_algorithm3_option2_on_robust_regression():
         if label == "large steps":
             assert fs[-1] < 0.95 * fs[0]
             assert abs(fs[-1] - ref["f"][-1]) <= 2e-3 * ref["f"][0]
+
+
+@pytest.mark.timeout(300)
+def test_graph_replayed_algorithm3_matches_eager():
+    """A whole iteration of Algorithm 3 (gradients, round, statistic, step, trial point, f at the
+    trial point, comparison step) recorded once into a HIP graph: each replay is the next
+    iteration, with accepts and rejects decided on the device, bit-identical to the eager loop."""
+    pr = workloads.robust_problem()
+    d = pr.A.shape[1]
+    rounds = 30
+    _say(f"graph-replayed Algorithm 3: d={d} m={pr.m} n={pr.n}, {rounds} rounds")
+    eager = coregd.RobustCoreGD(pr.A, pr.b, pr.n, pr.m, pr.seed)
+    r1, H = eager.r1 * 4e-3, eager.H * 1e-10           # steps large enough for rejections
+    trace = []
+    for k in range(rounds):
+        eager.round(k, r1=r1, H=H)
+        trace.append((eager.x.clone(), eager.f_cur.clone(), eager.accepted.clone(), eager.h.clone(), eager.p.clone()))
+    torch.cuda.synchronize()
+    flags = [int(t[2].item()) for t in trace]
+    assert 0 < sum(flags) < rounds, "the run should contain accepts and rejects"
+
+    run = coregd.RobustCoreGD(pr.A, pr.b, pr.n, pr.m, pr.seed)
+    graph = run.capture_round(r1=r1, H=H)
+    torch.cuda.synchronize()
+    assert run.round_dev.item() == 0 and float(run.x.abs().max()) == 0.0, "capture must not execute"
+    scratch = torch.zeros(1 << 14, device="cuda")
+    for k in range(rounds):
+        graph.replay()
+        if k % 4 == 1:                                   # eager work and a sync between replays
+            scratch.add_(1.0)
+            torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        x, f, acc, h, p = trace[k]
+        assert run.accepted.item() == acc.item(), f"replay {k}: accept flag"
+        assert torch.equal(run.x, x) and torch.equal(run.f_cur, f), f"replay {k}: iterate / objective"
+        assert torch.equal(run.h, h) and torch.equal(run.p, p), f"replay {k}: step / statistic"
+    assert run.round_dev.item() == rounds
