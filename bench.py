@@ -65,9 +65,23 @@ def cpu_baseline(case, d_s=1 << 20, m_s=256):
     G_host = np.ascontiguousarray(workloads.to_host(case.G[:, :d_s]))
     oracle.lib()
     t0 = time.perf_counter()
-    oracle.core_round(case.seed, 0, G_host, m_s)
+    _, pbar_ref, gt_ref = oracle.core_round(case.seed, 0, G_host, m_s)
     dt = time.perf_counter() - t0
+    # the same slice through the HIP path: the oracle's result is at hand, so report the parity too
+    G_s = case.G[:, :d_s].contiguous()
+    pbar, gtilde = core.core_round(case.seed, 0, G_s, m_s)
+    torch.cuda.synchronize()
+    if G_host.dtype == np.uint16:
+        G_f = (G_host.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        G_f = G_host.astype(np.float64)
+    norm = float(np.sqrt((G_f ** 2).sum(axis=1)).mean())
+    parity = {
+        "pbar_max_abs_err_over_norm_g": float(np.abs(pbar.cpu().numpy() - pbar_ref).max() / norm),
+        "gtilde_rel_l2": float(np.linalg.norm(gtilde.cpu().numpy() - gt_ref) / np.linalg.norm(gt_ref)),
+    }
     return {
+        "parity_on_sample": parity,
         "value": d_s * m_s * case.n / dt,
         "unit": "coords/s",
         "cores": 1,
