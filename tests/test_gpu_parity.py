@@ -105,6 +105,7 @@ SHAPES = [
     (1, 1, 1), (2, 3, 2), (3, 1, 3), (4, 2, 1), (5, 2, 1), (7, 5, 4), (8, 4, 2),
     (255, 16, 5), (256, 63, 8), (257, 64, 9), (1023, 65, 16), (1025, 255, 17),
     (4099, 257, 3), (5000, 300, 20), (20000, 1, 7), (70001, 513, 2), (12345, 1030, 33),
+    (3000, 130, 32), (2500, 70, 29), (2000, 65, 50), (1500, 64, 64),   # passes of up to 32 clients
 ]
 
 
