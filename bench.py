@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--variant", default="regenerate", choices=["regenerate", "materialized"],
                     help="materialized = the comparison variant that stores Xi while projecting and "
                          "reads it back to reconstruct (needs 4*d*m bytes of HBM)")
+    ap.add_argument("--clients", type=int, default=None,
+                    help="override the number of clients n of config4 / config5 (same recipe, more or fewer "
+                         "rows of G); the workload name in the output says so")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (3x) and exit; used to scale "
@@ -114,8 +117,16 @@ def main():
         return 0
     core.load_library()
 
-    case = {"config1": workloads.config1, "config2": workloads.config2_round, "config3": workloads.config3,
-            "config4": workloads.config4, "config5": workloads.config5}[args.workload](dev)
+    make = {"config1": workloads.config1, "config2": workloads.config2_round, "config3": workloads.config3,
+            "config4": workloads.config4, "config5": workloads.config5}[args.workload]
+    if args.clients is not None:
+        if args.workload not in ("config4", "config5") or args.clients < 1:
+            print("bench.py: --clients applies to config4 and config5 and must be >= 1", file=sys.stderr)
+            return 2
+        case = make(dev, n=args.clients)
+        case.name += f" with n overridden to {args.clients}"
+    else:
+        case = make(dev)
     d, m, n = case.d, case.m, case.n
     G = case.G
     ws = core.alloc_workspace(d, m, n, dev)
@@ -185,7 +196,7 @@ def main():
     # by what the same counters read for a 1 GiB copy: x2.000 and x1.000).  Counters cannot be read
     # from inside this process, so the figure is the one measured for the default workload and is
     # reported for that workload only: 410.9 MB fetched (G, once) + 66.8 MB written (partials).
-    traffic = 477.6e6 if (args.workload == "config4" and not mat) else None
+    traffic = 477.6e6 if (args.workload == "config4" and not mat and args.clients is None) else None
 
     out = {
         "metric": "projected coords/sec (d*m*n/s) for compress+reconstruct",
@@ -213,7 +224,8 @@ def main():
         "flop_equivalent_TFLOPs": pairs * (52 + 2 * (n + 1)) / (ms_per_step * 1e-3) / 1e12,
         "roofline": {
             "bound": "alu",
-            "kernel": "project_kernel (core_compress_batched: projection + cross-chunk sum)",
+            "kernel": ("project_kernel" if n <= 8 or mat else "project_mfma_kernel")
+                      + " (core_compress_batched: projection + cross-chunk sum)",
             "achieved": ach_proj / 1e12,
             "peak": PEAK_LANE_OPS / 1e12,
             "unit": "Tlaneop/s",
