@@ -157,8 +157,14 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
 // generator's VALU work, so the gain is small: measured ~4 % at 16 clients, a loss at 8.
 typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
 
+// Occupancy targets.  Left alone the compiler takes 112-180 registers for 3 to 8 client groups
+// (4 to 2 waves per SIMD); asking for more waves makes it reuse registers and the kernel is faster at
+// every width (measured at d = 2^23, m = 1024, bf16: 16 clients 6.31 -> 5.69 ms at 5 waves, 24 clients
+// 7.73 -> 7.15 ms at 3 waves, 32 clients 10.26 -> 8.94 ms at 3 waves; only the 8-group kernel then spills,
+// 23 registers of the tile prefetch).
 template <int NG, bool BF16>
-__global__ void __launch_bounds__(kThreads) project_mfma_kernel(ProjectArgs a)
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NG >= 6 ? 3 : NG >= 3 ? 5 : 1)))
+project_mfma_kernel(ProjectArgs a)
 {
     constexpr int NC = 4 * NG;
     constexpr int kRow = kTile + 4;   // 16-byte skew: the 4 client rows a wave reads hit distinct banks
