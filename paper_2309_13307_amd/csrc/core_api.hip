@@ -218,8 +218,8 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         const uint32_t left = n - c0;
         const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
         // Every pass regenerates the normals, so a pass takes as many clients as its kernel can
-        // hold: 32 on the matrix pipe (measured at 2^23 x 1024, bf16: n = 32 12.5 -> 10.3 ms,
-        // n = 50 22.1 -> 17.6 ms against passes of 16), 16 on the VALU.
+        // hold: 32 on the matrix pipe (measured at 2^23 x 1024, bf16: n = 32 12.5 -> 8.9 ms,
+        // n = 50 22.1 -> 15.9 ms against passes of 16), 16 on the VALU.
         const bool mfma = !store && use_mfma_projection(left);
         const uint32_t cap = mfma ? kMaxClientsPerPassMfma : kMaxClientsPerPass;
         const uint32_t nc = left < cap ? left : cap;
