@@ -150,6 +150,19 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
                       float *gtilde,
                       void *ws, size_t ws_bytes, core_stream stream);
 
+/* Reconstruction for nb machines at once, each from its own vector of (averaged) projections, as in
+ * decentralized CORE-GD (appendix) when the machines are batched on one device: the common vectors
+ * are generated once and feed all nb sums,
+ *   g_v[i]   = scale * sum_j P[v][j] xi_j[i]           v < nb, i < d
+ *   Gt[v][i] = g_v[i]                                   (if Gt != NULL)
+ *   X[v][i] -= h * g_v[i]                               (if X != NULL; in place)
+ *   P  [nb][ldp] device fp32, ldp >= m;  X, Gt [nb][ldx] device fp32, ldx >= d; at least one of X, Gt;
+ *   the three arrays must not overlap.  (The decentralized algorithm uses scale = n/m on the
+ *   averaged vector.) */
+int core_reconstruct_update_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t nb,
+                                    const float *P, uint64_t ldp, float scale, float h,
+                                    float *X, float *Gt, uint64_t ldx, core_stream stream);
+
 /* ---- round counter in device memory (for replayed launch sequences) --------------------------
  * Algorithms 1 and 2 draw fresh Gaussian vectors every round, so the round counter must change
  * from one round to the next.  A caller that records one iteration into a HIP graph and replays it

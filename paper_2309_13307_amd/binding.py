@@ -30,7 +30,7 @@ EXPORTS = (
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
     "core_accept_trial", "core_debug_plan", "core_round_update_r", "core_advance_round",
-    "core_round_trial_r",
+    "core_round_trial_r", "core_reconstruct_update_batched",
 )
 
 
@@ -99,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     L.core_round_trial_r.argtypes = [u64, vp, u64, u32, u32, vp, i32, u64, vp, f32, f64, f64, vp, vp, vp, vp,
                                      vp, vp, sz, vp]
     L.core_round_trial_r.restype = i32
+    L.core_reconstruct_update_batched.argtypes = [u64, u64, u64, u32, u32, vp, u64, f32, f32, vp, vp, u64, vp]
+    L.core_reconstruct_update_batched.restype = i32
     L.core_advance_round.argtypes = [vp, vp]
     L.core_advance_round.restype = i32
     L.core_debug_plan.argtypes = [u64, u32, u32, ctypes.POINTER(u64)]
@@ -359,6 +361,27 @@ def core_round_trial_r(seed: int, round_dev: torch.Tensor, G: torch.Tensor, m: i
                                            x.data_ptr(), x_trial.data_ptr(), _ptr(gtilde), ws.data_ptr(),
                                            ws.numel(), _stream())
     _check(rc, "core_round_trial_r")
+
+
+def core_reconstruct_update_batched(seed: int, rnd: int, P: torch.Tensor, scale: float, h: float,
+                                    X: torch.Tensor | None, Gt: torch.Tensor | None = None,
+                                    d: int | None = None) -> None:
+    """For every row v: g_v = scale * sum_j P[v][j] xi_j; Gt[v] = g_v and/or X[v] -= h * g_v."""
+    _require_cuda(P, X, Gt)
+    ref = X if X is not None else Gt
+    if ref is None:
+        raise ValueError("one of X, Gt is required")
+    for t_ in (P, X, Gt):
+        if t_ is not None and (t_.dim() != 2 or t_.stride(1) != 1 or t_.dtype != torch.float32):
+            raise ValueError("P, X, Gt must be 2-D float32 with unit stride along the last axis")
+    if X is not None and Gt is not None and (X.stride(0) != Gt.stride(0) or X.shape != Gt.shape):
+        raise ValueError("X and Gt must have the same shape and row stride")
+    nb, m = P.shape
+    if d is None:
+        d = ref.shape[1]
+    rc = load_library().core_reconstruct_update_batched(seed, rnd, d, m, nb, P.data_ptr(), P.stride(0), scale, h,
+                                                        _ptr(X), _ptr(Gt), ref.stride(0), _stream())
+    _check(rc, "core_reconstruct_update_batched")
 
 
 def core_advance_round(round_dev: torch.Tensor) -> None:

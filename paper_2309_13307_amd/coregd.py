@@ -122,16 +122,19 @@ class DecentralizedRidgeCoreGD:
         self.X = torch.zeros((n, d), dtype=torch.float32, device=device)
         self.ws = binding.alloc_workspace(d, m, n, device)
 
-    def round(self, k: int, h: float) -> None:
+    def round(self, k: int, h: float, batched: bool = True) -> None:
         r3 = torch.bmm(self.A3, self.X.unsqueeze(-1)) - self.b3                  # [n, rows/n, 1]
         G = (self.n * torch.bmm(self.A3.transpose(1, 2), r3).squeeze(-1) + self.lam * self.X).contiguous()
         P, _ = binding.core_compress_batched(self.seed, k, G, self.m, ws=self.ws)
         for _ in range(self.gossip_steps):
             P = self.W @ P
         P = P.contiguous()
-        for c in range(self.n):
-            binding.core_reconstruct_update(self.seed, k, P[c], self.n / self.m, h / self.n,
-                                            self.X[c], self.X[c])
+        if batched:     # the common vectors are generated once for all machines
+            binding.core_reconstruct_update_batched(self.seed, k, P, self.n / self.m, h / self.n, self.X)
+        else:
+            for c in range(self.n):
+                binding.core_reconstruct_update(self.seed, k, P[c], self.n / self.m, h / self.n,
+                                                self.X[c], self.X[c])
 
 
 class RobustCoreGD:

@@ -519,6 +519,34 @@ int core_advance_round(uint64_t* round_dev, core_stream stream)
     return CORE_OK;
 }
 
+int core_reconstruct_update_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t nb,
+                                    const float* P, uint64_t ldp, float scale, float h, float* X, float* Gt,
+                                    uint64_t ldx, core_stream stream)
+{
+    if (!P || (!X && !Gt) || d == 0 || d > kMaxD || m == 0 || nb == 0 || nb > kMaxN) return CORE_ERR_INVALID_ARGUMENT;
+    if (ldp < m || ldx < d) return CORE_ERR_INVALID_ARGUMENT;
+    if (X && Gt && intersects(X, (uint64_t)nb * ldx, Gt, (uint64_t)nb * ldx)) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects(P, (uint64_t)nb * ldp, X, (uint64_t)nb * ldx) || intersects(P, (uint64_t)nb * ldp, Gt, (uint64_t)nb * ldx))
+        return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(P, 4) || !aligned_to(X, 4) || !aligned_to(Gt, 4)) return CORE_ERR_MISALIGNED;
+    int rc = check_device();
+    if (rc != CORE_OK) return rc;
+    ReconBatchArgs a;
+    a.P = P; a.ldp = ldp; a.X = X; a.Gt = Gt; a.ldx = ldx; a.d = d; a.m = m; a.scale = scale; a.h = h;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
+    a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
+    const uint32_t blocks = (uint32_t)ceil_div(ceil_div(d, 4), (uint64_t)kThreads);
+    for (uint32_t v0 = 0; v0 < nb; v0 += 8) {
+        const uint32_t nv = (nb - v0 < 8u) ? (nb - v0) : 8u;
+        a.v0 = v0; a.nv = nv;
+        if (nv <= 4) hipLaunchKernelGGL((reconstruct_batched_kernel<4>), dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+        else         hipLaunchKernelGGL((reconstruct_batched_kernel<8>), dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return CORE_OK;
+}
+
 int core_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, double r1, double H,
                         float* p_out, float* h_out, core_stream stream)
 {

@@ -603,6 +603,98 @@ __global__ void __launch_bounds__(kThreads) accept_copy_kernel(const int32_t* ac
     }
 }
 
+// Reconstruction for several machines at once (decentralized CORE-GD with the machines batched on one
+// device: after gossip every machine holds its own averaged vector p_v and reconstructs from it with
+// the same xi_j).  The normals are generated once per (coordinate block, j) and feed NB accumulators,
+// the mirror image of the projection: X[v][i] -= h * scale * sum_j P[v][j] xi_j[i], or the sums
+// themselves into Gt.  Lanes over q, j the wave-uniform loop; P is staged in LDS as [j][NB] so that a
+// lane reads the NB factors of one j with NB/4 broadcast reads.
+struct ReconBatchArgs {
+    const float* P;       // [nb][ldp]
+    uint64_t ldp;
+    float* X;             // [nb][ldx] updated in place, or null
+    float* Gt;            // [nb][ldx] scale * sum, or null
+    uint64_t ldx;
+    uint64_t d;
+    uint32_t m;
+    uint32_t v0, nv;      // first machine of this pass, machines in this pass (<= NB)
+    float scale, h;
+    uint32_t k0, k1, r0, r1;
+};
+
+constexpr int kBatchPTile = 256;   // vectors j staged per step
+
+template <int NB>
+__global__ void __launch_bounds__(kThreads) reconstruct_batched_kernel(ReconBatchArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float pb[kBatchPTile][NB];
+    const uint32_t t = threadIdx.x;
+    const uint64_t nblk = (a.d + 3) / 4;
+    const uint64_t q64 = (uint64_t)blockIdx.x * kThreads + t;
+    const uint32_t q = (uint32_t)q64;
+
+    Generator<2, 3> gen;
+    gen.init(a.k0, a.k1, a.r0, a.r1);
+
+    float outer[NB][4];
+#pragma unroll
+    for (int v = 0; v < NB; ++v)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) outer[v][k] = 0.0f;
+
+    for (uint32_t j0 = 0; j0 < a.m; j0 += kBatchPTile) {
+        const uint32_t jn = (a.m - j0 < (uint32_t)kBatchPTile) ? (a.m - j0) : (uint32_t)kBatchPTile;
+        __syncthreads();
+        for (uint32_t x = t; x < jn * NB; x += kThreads) {
+            const uint32_t jj = x / NB, v = x % NB;
+            pb[jj][v] = (v < a.nv) ? a.P[(uint64_t)(a.v0 + v) * a.ldp + j0 + jj] : 0.0f;
+        }
+        __syncthreads();
+        // inner sums of 64 vectors, then added to the running sum: keeps fp32 chains short
+        for (uint32_t jb = 0; jb < jn; jb += 64) {
+            const uint32_t je = (jn - jb < 64u) ? (jn - jb) : 64u;
+            float acc[NB][4];
+#pragma unroll
+            for (int v = 0; v < NB; ++v)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[v][k] = 0.0f;
+            for (uint32_t jj = 0; jj < je; ++jj) {
+                float z0, z1, z2, z3;
+                gen.block(q, j0 + jb + jj, z0, z1, z2, z3);
+#pragma unroll
+                for (int v = 0; v < NB; ++v) {
+                    const float p = pb[jb + jj][v];
+                    acc[v][0] = fmaf(p, z0, acc[v][0]);
+                    acc[v][1] = fmaf(p, z1, acc[v][1]);
+                    acc[v][2] = fmaf(p, z2, acc[v][2]);
+                    acc[v][3] = fmaf(p, z3, acc[v][3]);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < NB; ++v)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) outer[v][k] += acc[v][k];
+        }
+    }
+
+    if (q64 >= nblk) return;
+    const uint64_t i = 4 * q64;
+    const float sc = a.scale * kXiScale;
+#pragma unroll
+    for (int v = 0; v < NB; ++v) {
+        if ((uint32_t)v >= a.nv) break;
+        const uint64_t row = (uint64_t)(a.v0 + v) * a.ldx;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i + k < a.d) {
+                const float g = sc * outer[v][k];
+                if (a.Gt) a.Gt[row + i + k] = g;
+                if (a.X) a.X[row + i + k] = fmaf(-a.h, g, a.X[row + i + k]);
+            }
+        }
+    }
+}
+
 // Device-resident round counter for replayed launch sequences (HIP graphs): one thread adds 1.
 __global__ void advance_round_kernel(uint64_t* round_dev)
 {

@@ -205,6 +205,23 @@ def test_header_compiles_and_links_from_plain_c(tmp_path):
     assert "c client ok" in res.stdout
 
 
+def test_batched_reconstruction_arguments():
+    L = core.load_library()
+    E = binding
+    f = L.core_reconstruct_update_batched
+    P, X, G = FAKE, FAKE + 0x10000, FAKE + 0x20000          # 4 x 16 and 4 x 1024 floats
+    assert f(1, 0, 1024, 16, 4, None, 16, 0.25, 0.1, X, None, 1024, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, P, 16, 0.25, 0.1, None, None, 1024, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 0, P, 16, 0.25, 0.1, X, None, 1024, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, P, 15, 0.25, 0.1, X, None, 1024, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, P, 16, 0.25, 0.1, X, None, 1023, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, P, 16, 0.25, 0.1, X, X + 4096, 1024, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, X + 64, 16, 0.25, 0.1, X, None, 1024, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, P, 16, 0.25, 0.1, X + 2, G, 1024, None) == E.ERR_MISALIGNED
+    if not torch.cuda.is_available():
+        assert f(1, 0, 1024, 16, 4, P, 16, 0.25, 0.1, X, G, 1024, None) == E.ERR_NO_DEVICE
+
+
 def test_device_round_counter_arguments():
     L = core.load_library()
     E = binding

@@ -477,3 +477,41 @@ def test_host_threads_with_their_own_streams():
     for t in range(nthreads):
         for r in range(rounds):
             assert torch.equal(results[t][r][0], refs[r][0]) and torch.equal(results[t][r][1], refs[r][1]), (t, r)
+
+
+@pytest.mark.parametrize("d,m,nb,pad", [(1, 1, 1, 0), (4099, 7, 3, 0), (5000, 300, 4, 0), (20003, 65, 5, 5),
+                                        (70001, 257, 8, 0), (12345, 64, 9, 3), (3000, 1030, 17, 0)])
+def test_batched_reconstruction(d, m, nb, pad):
+    """nb machines reconstruct from their own projection vectors with one generation of the common
+    vectors: every row against the oracle's single-vector reconstruction, with and without the
+    fused step, on padded (strided) arrays."""
+    _say(f"batched reconstruction d={d} m={m} nb={nb} pad={pad}")
+    rng = np.random.default_rng(d + m + nb)
+    P_host = rng.standard_normal((nb, m)).astype(np.float32)
+    X_host = rng.standard_normal((nb, d)).astype(np.float32)
+    Pbuf = torch.zeros((nb, m + pad), device=DEV)
+    Pbuf[:, :m] = torch.from_numpy(P_host).to(DEV)
+    P = Pbuf[:, :m]
+    Xbuf = torch.full((nb, d + pad), 7.0, device=DEV)
+    Xbuf[:, :d] = torch.from_numpy(X_host).to(DEV)
+    Gbuf = torch.full((nb, d + pad), -3.0, device=DEV)
+    X, Gt = Xbuf[:, :d], Gbuf[:, :d]
+    seed, rnd, scale, h = 21, 4, nb / m, 0.25
+    core.core_reconstruct_update_batched(seed, rnd, P, scale, h, X, Gt)
+    Gonly = torch.zeros((nb, d), device=DEV)
+    core.core_reconstruct_update_batched(seed, rnd, P, scale, 0.0, None, Gonly)
+    Xonly = torch.from_numpy(X_host).to(DEV)
+    core.core_reconstruct_update_batched(seed, rnd, P, scale, h, Xonly, None)
+    _sync()
+    assert torch.equal(Gonly, Gt.contiguous()) and torch.equal(Xonly, X.contiguous())
+    if pad:
+        assert float((Xbuf[:, d:] - 7.0).abs().max()) == 0.0 and float((Gbuf[:, d:] + 3.0).abs().max()) == 0.0
+    for v in range(nb):
+        ref = oracle.reconstruct(seed, rnd, P_host[v].astype(np.float64), scale, 0, d)
+        parity.check_gtilde(Gt[v].cpu().numpy(), ref, f"row {v}")
+        step = X_host[v].astype(np.float64) - X[v].cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(step - h * ref) <= 1e-5 * np.linalg.norm(h * ref) + 1.2e-7 * np.linalg.norm(X_host[v])
+    # one row through the single-vector entry point: same values up to the order of two roundings
+    single = core.core_reconstruct(seed, rnd, d, P[0].contiguous(), scale)
+    _sync()
+    assert parity.rel_l2(single.cpu().numpy(), Gt[0].cpu().numpy()) < 1e-6
