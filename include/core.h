@@ -31,11 +31,16 @@
  *     bit-identical from run to run on the same device and build (all sums run
  *     in a fixed order; no floating-point atomics).
  *   - Return value: CORE_OK (0) or a negative CORE_ERR_* code.  Arguments are
- *     validated on the host before anything is launched, so a failing call
- *     enqueues nothing and writes nothing.
- *   - Limits: 1 <= d <= 2^34, 1 <= m <= 2^32-1, 1 <= n <= 65535, ld >= d, and
+ *     validated on the host before anything is launched, so a call that fails
+ *     validation enqueues nothing and writes nothing.  CORE_ERR_HIP is the one
+ *     exception: it reports that the runtime refused a launch, and an entry point
+ *     that issues several launches may already have enqueued the earlier ones
+ *     (its outputs are then undefined).  Launch status is taken from the launch
+ *     call itself, never from the thread's sticky last-error state.
+ *   - Limits: 1 <= d <= 2^34, 1 <= m <= 2^32-1024, 1 <= n <= 65535, ld >= d, and
  *     ceil(d / 2^18) * ceil(m / 256) < 2^31 (one projection block per 2^18 coordinates x 256
- *     vectors at the largest sizes; d * m below ~1.4e17 always qualifies).
+ *     vectors at the largest sizes; d * m below ~1.4e17 always qualifies).  Sizes outside
+ *     the limits are refused with CORE_ERR_INVALID_ARGUMENT by every entry point.
  *     fp32 pointers must be 4-byte aligned, bf16 pointers 2-byte aligned; rows of G
  *     may start at any element.  gtilde is written with 128-bit stores when it is
  *     16-byte aligned and with scalar stores otherwise.
@@ -76,6 +81,11 @@ const char *core_strerror(int code);
 
 /* hipError_t of the most recent CORE_ERR_HIP on the calling thread (0 if none). */
 int core_last_hip_error(void);
+
+/* Identifier of the sources the library was built from (a hash set by the build step, or
+ * "unknown").  Static string.  A loader can compare it with the sources it has at hand and
+ * refuse, or rebuild, a stale binary. */
+const char *core_build_id(void);
 
 /* Bytes of device scratch the compress/round entry points need for these sizes
  * (per-chunk partial projections and the staged cross-chunk sums).  Returns 0 if
@@ -158,7 +168,12 @@ int core_round_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uin
  *   X[v][i] -= h * g_v[i]                               (if X != NULL; in place)
  *   P  [nb][ldp] device fp32, ldp >= m;  X, Gt [nb][ldx] device fp32, ldx >= d; at least one of X, Gt;
  *   the three arrays must not overlap.  (The decentralized algorithm uses scale = n/m on the
- *   averaged vector.) */
+ *   averaged vector.)
+ * The library's share of the decentralized algorithm is the projection (core_compress_batched with
+ * P requested) and this reconstruction.  The exchange between the two -- every machine averaging
+ * its neighbours' projection vectors with the gossip matrix -- is the caller's: on real hardware
+ * it is the network step, and with the machines batched on one device it is one small product
+ * W * P that the caller forms before this call. */
 int core_reconstruct_update_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t nb,
                                     const float *P, uint64_t ldp, float scale, float h,
                                     float *X, float *Gt, uint64_t ldx, core_stream stream);
@@ -289,9 +304,30 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
  * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */
 int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6]);
 
-/* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks.  out device uint32. */
+/* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks <= 2^28.  out device uint32.
+ * (Layout 0 of core_debug_philox_layout with one vector.) */
 int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,
                       uint32_t *out, core_stream stream);
+
+/* The same words for nj vectors x nq blocks, out[jj][qq][0..3] = words of block q0 + qq of vector
+ * j0 + jj (Algorithm 1, REQUIRE line: every machine must draw the same stream, so the words must
+ * equal the reference generator's bit for bit), produced with the generator instantiation and
+ * lane layout of one family of production kernels:
+ *   layout 0  every round key on the scalar path, one thread per block
+ *   layout 1  the projection kernels: lanes over vectors, the block index wave-uniform
+ *   layout 2  the reconstruction kernels and the small-problem projection: lanes over blocks, the
+ *             vector index wave-uniform
+ *   layout 3  the generator of core_debug_xi
+ * j0 + nj <= 2^32, q0 + nq <= 2^32, nj * nq <= 2^28.  out device uint32 [nj][nq][4]. */
+int core_debug_philox_layout(int layout, uint64_t seed, uint64_t round, uint32_t j0, uint32_t nj,
+                             uint64_t q0, uint64_t nq, uint32_t *out, core_stream stream);
+
+/* Force the projection kernel for every later call in this process (A/B measurements and tests
+ * that drive each kernel over each shape): 0 = the library's own choice, 1 = vector-ALU kernel
+ * with lanes over vectors, 2 = matrix-pipe kernel, 3 = lanes-over-coordinates kernel.  The
+ * environment variable CORE_PROJECT_VARIANT = valu | mfma | q sets the initial value; it is read
+ * once.  Not synchronised with calls in flight on other host threads. */
+int core_debug_set_projection(int variant);
 
 /* out[t] = xi_j[i0 + t] as the kernels compute it (fp32), t < count.  out device fp32. */
 int core_debug_xi(uint64_t seed, uint64_t round, uint32_t j, uint64_t i0, uint64_t count,

@@ -30,7 +30,8 @@ EXPORTS = (
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
     "core_accept_trial", "core_debug_plan", "core_round_update_r", "core_advance_round",
-    "core_round_trial_r", "core_reconstruct_update_batched",
+    "core_round_trial_r", "core_reconstruct_update_batched", "core_build_id",
+    "core_debug_philox_layout", "core_debug_set_projection",
 )
 
 
@@ -44,11 +45,17 @@ _lib = None
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libcore_hip.so, building it only if no built library is present."""
+    """Load libcore_hip.so.  A library built from the sources at hand is loaded as it is; a missing
+    or stale one (its build id differs from the hash of the sources) is rebuilt first, and if there
+    is no compiler to do that the call fails rather than run an outdated binary."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
+    if _build.is_stale():
+        have, want = _build.built_id(), _build.source_id()
+        if not os.path.exists(_build.hipcc_path()):
+            raise RuntimeError(f"libcore_hip.so is {'missing' if have is None else 'stale'} (build id {have}, "
+                               f"sources {want}) and there is no hipcc to build it")
         _build.build_library()
     L = ctypes.CDLL(_build.LIB_PATH)
     u64, u32, i32, vp, sz, f32 = (ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p,
@@ -107,6 +114,12 @@ def load_library() -> ctypes.CDLL:
     L.core_debug_plan.restype = i32
     L.core_debug_philox.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     L.core_debug_philox.restype = i32
+    L.core_debug_philox_layout.argtypes = [i32, u64, u64, u32, u32, u64, u64, vp, vp]
+    L.core_debug_philox_layout.restype = i32
+    L.core_debug_set_projection.argtypes = [i32]
+    L.core_debug_set_projection.restype = i32
+    L.core_build_id.argtypes = []
+    L.core_build_id.restype = ctypes.c_char_p
     L.core_debug_xi.argtypes = [u64, u64, u32, u64, u64, vp, vp]
     L.core_debug_xi.restype = i32
     _lib = L
@@ -474,6 +487,32 @@ def core_debug_philox(seed: int, rnd: int, j: int, q0: int, nblocks: int, device
     rc = load_library().core_debug_philox(seed, rnd, j, q0, nblocks, out.data_ptr(), _stream())
     _check(rc, "core_debug_philox")
     return out
+
+
+PHILOX_LAYOUTS = {"scalar_keys": 0, "projection": 1, "reconstruction": 2, "debug_xi": 3}
+
+
+def core_debug_philox_layout(layout: str | int, seed: int, rnd: int, j0: int, nj: int, q0: int, nq: int,
+                             device="cuda") -> torch.Tensor:
+    """Words [nj, nq, 4] of blocks q0.. of vectors j0.., generated the way one kernel family does."""
+    code = PHILOX_LAYOUTS[layout] if isinstance(layout, str) else int(layout)
+    out = torch.empty((nj, nq, 4), dtype=torch.int32, device=device)
+    rc = load_library().core_debug_philox_layout(code, seed, rnd, j0, nj, q0, nq, out.data_ptr(), _stream())
+    _check(rc, "core_debug_philox_layout")
+    return out
+
+
+PROJECTION_VARIANTS = {"default": 0, "valu": 1, "mfma": 2, "q": 3}
+
+
+def core_debug_set_projection(variant: str | int) -> None:
+    """Force the projection kernel for later calls ("default" hands the choice back)."""
+    code = PROJECTION_VARIANTS[variant] if isinstance(variant, str) else int(variant)
+    _check(load_library().core_debug_set_projection(code), "core_debug_set_projection")
+
+
+def core_build_id() -> str:
+    return load_library().core_build_id().decode()
 
 
 def core_debug_xi(seed: int, rnd: int, j: int, i0: int, count: int, device="cuda") -> torch.Tensor:

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#include <atomic>
 #include <cmath>
 
 #include "../../include/core.h"
@@ -15,7 +16,17 @@ using namespace core;
 
 thread_local int g_last_hip_error = 0;
 
+// Identifies the sources this binary was built from (set by the build step; the marker prefix lets
+// a loader find the id in the file without loading it).
+#ifndef CORE_BUILD_ID
+#define CORE_BUILD_ID "unknown"
+#endif
+const char kBuildId[] = "CORE_BUILD_ID=" CORE_BUILD_ID;
+
 constexpr uint64_t kMaxD = 1ull << 34;
+// The kernels walk the vectors with 32-bit counters in steps of up to 1024; the cap keeps
+// `j0 += step` from wrapping before `j0 < m` turns false.
+constexpr uint32_t kMaxM = 0xFFFFFFFFu - 1023u;   // 2^32 - 1024
 constexpr uint32_t kMaxN = 65535u;
 constexpr uint32_t kMaxClientsPerPass = 16;       // VALU projection: accumulators held in registers per lane
 constexpr uint32_t kMaxClientsPerPassMfma = 32;   // matrix-pipe projection (8 groups of 4 clients)
@@ -46,13 +57,37 @@ constexpr uint64_t kMaxGridBlocks = 0x7fffffffull;   // HIP's limit on gridDim.x
 // four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens out speed differences
 // between CUs.  With fewer than 64 vectors, or too little work to fill the chip that way, the
 // lanes-over-q projection is planned instead.  Sizes depend only on (d, m, n).
+// Which projection kernel to use: the library's own choice, or one forced for A/B runs and for
+// the tests that drive every kernel over every shape.  Set with core_debug_set_projection (a
+// test-only export); the environment variable CORE_PROJECT_VARIANT=valu|mfma|q gives the initial
+// value and is read once per process.
+enum Variant : int { kVariantAuto = 0, kVariantValu = 1, kVariantMfma = 2, kVariantQ = 3 };
+
+int variant_from_env()
+{
+    const char* v = getenv("CORE_PROJECT_VARIANT");
+    if (!v) return kVariantAuto;
+    if (strcmp(v, "valu") == 0) return kVariantValu;
+    if (strcmp(v, "mfma") == 0) return kVariantMfma;
+    if (strcmp(v, "q") == 0) return kVariantQ;
+    return kVariantAuto;
+}
+
+std::atomic<int>& variant_cell()
+{
+    static std::atomic<int> cell{variant_from_env()};
+    return cell;
+}
+
+inline int forced_variant() { return variant_cell().load(std::memory_order_relaxed); }
+
 bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
 {
-    if (d == 0 || d > kMaxD || m == 0 || n == 0 || n > kMaxN) return false;
+    if (d == 0 || d > kMaxD || m == 0 || m > kMaxM || n == 0 || n > kMaxN) return false;
     const uint64_t tiles_total = ceil_div(d, kTile);
-    const char* forced = getenv("CORE_PROJECT_VARIANT");   // A/B switch: valu | mfma | q
-    if (forced && strcmp(forced, "q") == 0) p.qmode = allow_qmode;
-    else if (forced && (strcmp(forced, "valu") == 0 || strcmp(forced, "mfma") == 0)) p.qmode = false;
+    const int forced = forced_variant();
+    if (forced == kVariantQ) p.qmode = allow_qmode;
+    else if (forced == kVariantValu || forced == kVariantMfma) p.qmode = false;
     else p.qmode = allow_qmode && (m < 64 || ceil_div(m, 64) * tiles_total <= 1024);
     if (p.qmode) {
         const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
@@ -103,14 +138,30 @@ int hip_fail(hipError_t e)
     return CORE_ERR_HIP;
 }
 
+// Whether the process has a usable GPU: asked of the runtime once, then remembered.
 int check_device()
 {
-    int count = 0;
-    if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
-        (void)hipGetLastError();
-        return CORE_ERR_NO_DEVICE;
-    }
-    return CORE_OK;
+    static const int rc = [] {
+        int count = 0;
+        if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) {
+            (void)hipGetLastError();
+            return (int)CORE_ERR_NO_DEVICE;
+        }
+        return (int)CORE_OK;
+    }();
+    return rc;
+}
+
+// One kernel launch whose status is the return value of the launch call itself, so an error
+// left behind by some earlier HIP call on this thread is never mistaken for a failure here.
+template <typename T> struct same_type { using type = T; };
+
+template <typename... Params>
+hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t st,
+                  typename same_type<Params>::type... args)
+{
+    void* ptrs[] = {(void*)&args...};
+    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
 }
 
 bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -119,43 +170,36 @@ template <int NC>
 hipError_t launch_project(const ProjectArgs& a, bool bf16, bool store_xi, uint32_t blocks, hipStream_t st)
 {
     const dim3 g(blocks), b(kThreads);
-    if (store_xi) {
-        if (bf16) hipLaunchKernelGGL((project_kernel<NC, true, true>), g, b, 0, st, a);
-        else      hipLaunchKernelGGL((project_kernel<NC, false, true>), g, b, 0, st, a);
-    } else {
-        if (bf16) hipLaunchKernelGGL((project_kernel<NC, true, false>), g, b, 0, st, a);
-        else      hipLaunchKernelGGL((project_kernel<NC, false, false>), g, b, 0, st, a);
-    }
-    return hipGetLastError();
+    if (store_xi) return bf16 ? launch(project_kernel<NC, true, true>, g, b, st, a)
+                              : launch(project_kernel<NC, false, true>, g, b, st, a);
+    return bf16 ? launch(project_kernel<NC, true, false>, g, b, st, a)
+                : launch(project_kernel<NC, false, false>, g, b, st, a);
 }
 
 template <int NG>
 hipError_t launch_project_mfma(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
 {
     const dim3 g(blocks), b(kThreads);
-    if (bf16) hipLaunchKernelGGL((project_mfma_kernel<NG, true>), g, b, 0, st, a);
-    else      hipLaunchKernelGGL((project_mfma_kernel<NG, false>), g, b, 0, st, a);
-    return hipGetLastError();
+    return bf16 ? launch(project_mfma_kernel<NG, true>, g, b, st, a)
+                : launch(project_mfma_kernel<NG, false>, g, b, st, a);
 }
 
 template <int NC>
 hipError_t launch_project_q(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
 {
     const dim3 g(blocks), b(kThreads);
-    if (bf16) hipLaunchKernelGGL((project_q_kernel<NC, true>), g, b, 0, st, a);
-    else      hipLaunchKernelGGL((project_q_kernel<NC, false>), g, b, 0, st, a);
-    return hipGetLastError();
+    return bf16 ? launch(project_q_kernel<NC, true>, g, b, st, a)
+                : launch(project_q_kernel<NC, false>, g, b, st, a);
 }
 
-// Which projection kernel serves a pass of nc clients.  Measured on MI355X (config 5, n = 16):
-// the matrix-pipe kernel is ~4 % faster than the VALU kernel at 16 clients and ~5 % slower at 8,
-// so it is the default above 8 clients.  CORE_PROJECT_VARIANT=valu|mfma forces one for A/B runs
-// (and =q forces the lanes-over-q kernel, see make_plan).
+// Which projection kernel serves a pass of nc clients.  Measured on MI355X (GPT-2-sized
+// gradient, n = 16): the matrix-pipe kernel is ~4 % faster than the VALU kernel at 16 clients and
+// ~5 % slower at 8, so it is the default above 8 clients.
 bool use_mfma_projection(uint32_t nc)
 {
-    const char* v = getenv("CORE_PROJECT_VARIANT");
-    if (v && strcmp(v, "mfma") == 0) return true;
-    if (v && strcmp(v, "valu") == 0) return false;
+    const int forced = forced_variant();
+    if (forced == kVariantMfma) return true;
+    if (forced == kVariantValu) return false;
     return nc > 8;
 }
 
@@ -176,7 +220,7 @@ int validate_compress(uint64_t d, uint32_t m, uint32_t n, const void* G, core_dt
 int validate_reconstruct(uint64_t d, uint32_t m, const float* pbar, const float* gtilde)
 {
     if (!pbar || !gtilde) return CORE_ERR_INVALID_ARGUMENT;
-    if (d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (d == 0 || d > kMaxD || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4) || !aligned_to(gtilde, 4)) return CORE_ERR_MISALIGNED;
     return CORE_OK;
 }
@@ -247,21 +291,16 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     hipError_t e;
     if (plan.nchunks <= 16) {
         // few chunks: one kernel sums them and the clients
-        hipLaunchKernelGGL(reduce_clients_kernel<float>, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), 0, st,
-                           part, m, n, plan.nchunks, P, pbar);
-        e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e);
-        return CORE_OK;
+        e = launch(reduce_clients_kernel<float>, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), st,
+                   (const float*)part, m, n, plan.nchunks, P, pbar);
+        return e == hipSuccess ? CORE_OK : hip_fail(e);
     }
-    hipLaunchKernelGGL(reduce_chunks_kernel, dim3((uint32_t)ceil_div(m, 32), n, plan.Z), dim3(kThreads), 0, st,
-                       part, m, n, plan.nchunks, psum);
-    e = hipGetLastError();
+    e = launch(reduce_chunks_kernel, dim3((uint32_t)ceil_div(m, 32), n, plan.Z), dim3(kThreads), st,
+               (const float*)part, m, n, plan.nchunks, psum);
     if (e != hipSuccess) return hip_fail(e);
-    hipLaunchKernelGGL(reduce_clients_kernel<double>, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), 0, st,
-                       psum, m, n, plan.Z, P, pbar);
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e);
-    return CORE_OK;
+    e = launch(reduce_clients_kernel<double>, dim3((uint32_t)ceil_div(m, 32)), dim3(kThreads), st,
+               (const double*)psum, m, n, plan.Z, P, pbar);
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 
 struct UpdateArgs {
@@ -298,16 +337,10 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     const bool two = ceil_div(nblk, (uint64_t)kThreads * 2) >= 2 * kBlockSlots;
     const uint32_t blocks = (uint32_t)ceil_div(nblk, (uint64_t)kThreads * (two ? 2 : 1));
     const dim3 g(blocks), b(kThreads);
-    if (up) {
-        if (two) hipLaunchKernelGGL((reconstruct_kernel<true, 2>), g, b, 0, st, a);
-        else     hipLaunchKernelGGL((reconstruct_kernel<true, 1>), g, b, 0, st, a);
-    } else {
-        if (two) hipLaunchKernelGGL((reconstruct_kernel<false, 2>), g, b, 0, st, a);
-        else     hipLaunchKernelGGL((reconstruct_kernel<false, 1>), g, b, 0, st, a);
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e);
-    return CORE_OK;
+    hipError_t e;
+    if (up) e = two ? launch(reconstruct_kernel<true, 2>, g, b, st, a) : launch(reconstruct_kernel<true, 1>, g, b, st, a);
+    else    e = two ? launch(reconstruct_kernel<false, 2>, g, b, st, a) : launch(reconstruct_kernel<false, 1>, g, b, st, a);
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 
 // [a, a + na floats) and [b, b + nb floats) share at least one element (null never does)
@@ -343,7 +376,7 @@ int validate_update(uint64_t d, const float* y, const float* x_new, const float*
 int validate_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, double r1, double H,
                             const float* p_out, const float* h_out)
 {
-    if (!pbar || !h_out || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!pbar || !h_out || d == 0 || d > kMaxD || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
     if (!(c > 0.0f) || !(r1 > 0.0) || !(H > 0.0)) return CORE_ERR_INVALID_ARGUMENT;
     if (h_out == p_out || h_out == pbar || p_out == pbar) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4) || !aligned_to(p_out, 4) || !aligned_to(h_out, 4)) return CORE_ERR_MISALIGNED;
@@ -355,11 +388,9 @@ int enqueue_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, d
 {
     const double first = (double)m / (16.0 * r1);
     const double second = std::pow(H, -0.5) * std::pow((double)d, -0.75) * std::pow((double)m, 0.75) / 1600.0;
-    hipLaunchKernelGGL(nonconvex_step_kernel, dim3(1), dim3(kThreads), 0, st, pbar, m, c, (float)first,
-                       (float)second, p_out, h_out);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e);
-    return CORE_OK;
+    const hipError_t e = launch(nonconvex_step_kernel, dim3(1), dim3(kThreads), st, pbar, m, c, (float)first,
+                                (float)second, p_out, h_out);
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 
 int validate_trial(uint64_t d, const float* h, const float* x, const float* x_trial, const float* gtilde)
@@ -378,15 +409,14 @@ int enqueue_reconstruct_xi(uint64_t d, uint32_t m, const float* pbar, float scal
     ReconXiArgs a;
     a.pbar = pbar; a.xi = xi; a.gtilde = gtilde; a.d = d; a.m = m; a.scale = scale;
     const uint64_t nblk = ceil_div(d, 4);
-    hipLaunchKernelGGL(reconstruct_xi_kernel, dim3((uint32_t)ceil_div(nblk, kThreads / 64)), dim3(kThreads), 0, st, a);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch(reconstruct_xi_kernel, dim3((uint32_t)ceil_div(nblk, kThreads / 64)), dim3(kThreads), st, a);
     return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 
 // bytes of the materialised Xi for (d, m); 0 if it cannot be addressed
 size_t xi_bytes(uint64_t d, uint32_t m)
 {
-    if (d == 0 || d > kMaxD || m == 0) return 0;
+    if (d == 0 || d > kMaxD || m == 0 || m > kMaxM) return 0;
     const uint64_t nblk = ceil_div(d, 4);
     if (nblk > (~(uint64_t)0) / 16 / m) return 0;
     if (ceil_div(nblk, kThreads / 64) > 0x7fffffffull) return 0;
@@ -396,6 +426,8 @@ size_t xi_bytes(uint64_t d, uint32_t m)
 }  // namespace
 
 extern "C" {
+
+const char* core_build_id(void) { return kBuildId + 14; }
 
 const char* core_strerror(int code)
 {
@@ -459,7 +491,7 @@ int core_reconstruct_update(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
                             float scale, float h, const float* y, float* x_new, const float* x_cur,
                             float one_minus_beta, float* y_next, float* gtilde, core_stream stream)
 {
-    if (!pbar || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!pbar || d == 0 || d > kMaxD || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4)) return CORE_ERR_MISALIGNED;
     int rc = validate_update(d, y, x_new, x_cur, y_next, gtilde);
     if (rc != CORE_OK) return rc;
@@ -513,17 +545,15 @@ int core_advance_round(uint64_t* round_dev, core_stream stream)
     if (!aligned_to(round_dev, 8)) return CORE_ERR_MISALIGNED;
     int rc = check_device();
     if (rc != CORE_OK) return rc;
-    hipLaunchKernelGGL(advance_round_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, round_dev);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e);
-    return CORE_OK;
+    const hipError_t e = launch(advance_round_kernel, dim3(1), dim3(64), (hipStream_t)stream, round_dev);
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 
 int core_reconstruct_update_batched(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t nb,
                                     const float* P, uint64_t ldp, float scale, float h, float* X, float* Gt,
                                     uint64_t ldx, core_stream stream)
 {
-    if (!P || (!X && !Gt) || d == 0 || d > kMaxD || m == 0 || nb == 0 || nb > kMaxN) return CORE_ERR_INVALID_ARGUMENT;
+    if (!P || (!X && !Gt) || d == 0 || d > kMaxD || m == 0 || m > kMaxM || nb == 0 || nb > kMaxN) return CORE_ERR_INVALID_ARGUMENT;
     if (ldp < m || ldx < d) return CORE_ERR_INVALID_ARGUMENT;
     if (X && Gt && intersects(X, (uint64_t)nb * ldx, Gt, (uint64_t)nb * ldx)) return CORE_ERR_INVALID_ARGUMENT;
     if (intersects(P, (uint64_t)nb * ldp, X, (uint64_t)nb * ldx) || intersects(P, (uint64_t)nb * ldp, Gt, (uint64_t)nb * ldx))
@@ -539,9 +569,8 @@ int core_reconstruct_update_batched(uint64_t seed, uint64_t round, uint64_t d, u
     for (uint32_t v0 = 0; v0 < nb; v0 += 8) {
         const uint32_t nv = (nb - v0 < 8u) ? (nb - v0) : 8u;
         a.v0 = v0; a.nv = nv;
-        if (nv <= 4) hipLaunchKernelGGL((reconstruct_batched_kernel<4>), dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
-        else         hipLaunchKernelGGL((reconstruct_batched_kernel<8>), dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
-        hipError_t e = hipGetLastError();
+        const hipError_t e = nv <= 4 ? launch(reconstruct_batched_kernel<4>, dim3(blocks), dim3(kThreads), (hipStream_t)stream, a)
+                                     : launch(reconstruct_batched_kernel<8>, dim3(blocks), dim3(kThreads), (hipStream_t)stream, a);
         if (e != hipSuccess) return hip_fail(e);
     }
     return CORE_OK;
@@ -558,7 +587,7 @@ int core_nonconvex_step(uint64_t d, uint32_t m, const float* pbar, float c, doub
 
 int core_step_size_option2(uint64_t d, uint32_t m, double r1, double H, double L, double Delta, double* h)
 {
-    if (!h || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!h || d == 0 || d > kMaxD || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
     if (!(r1 > 0.0) || !(H > 0.0) || !(L > 0.0) || !(Delta > 0.0)) return CORE_ERR_INVALID_ARGUMENT;
     const double first = (double)m / (16.0 * r1);
     const double second = std::pow(H, -0.5) * std::pow(L * Delta, -0.25) * std::pow((double)d, -0.75) *
@@ -571,7 +600,7 @@ int core_reconstruct_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m
                            float scale, const float* h, const float* x, float* x_trial, float* gtilde,
                            core_stream stream)
 {
-    if (!pbar || d == 0 || d > kMaxD || m == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!pbar || d == 0 || d > kMaxD || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4)) return CORE_ERR_MISALIGNED;
     int rc = validate_trial(d, h, x, x_trial, gtilde);
     if (rc != CORE_OK) return rc;
@@ -634,15 +663,12 @@ int core_accept_trial(uint64_t d, float* f_cur, const float* f_trial, float* x, 
     int rc = check_device();
     if (rc != CORE_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(1), dim3(64), 0, st, f_cur, f_trial, accepted);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch(accept_decide_kernel, dim3(1), dim3(64), st, f_cur, f_trial, accepted);
     if (e != hipSuccess) return hip_fail(e);
     const int vec = (aligned_to(x, 16) && aligned_to(x_trial, 16)) ? 1 : 0;
     const uint32_t blocks = (uint32_t)ceil_div(ceil_div(d, 4), (uint64_t)kThreads);
-    hipLaunchKernelGGL(accept_copy_kernel, dim3(blocks), dim3(kThreads), 0, st, accepted, x, x_trial, d, vec);
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e);
-    return CORE_OK;
+    e = launch(accept_copy_kernel, dim3(blocks), dim3(kThreads), st, (const int32_t*)accepted, x, x_trial, d, vec);
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 
 size_t core_xi_bytes(uint64_t d, uint32_t m) { return xi_bytes(d, m); }
@@ -710,19 +736,44 @@ int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6])
     return CORE_OK;
 }
 
-int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,
-                      uint32_t* out, core_stream stream)
+int core_debug_philox_layout(int layout, uint64_t seed, uint64_t round, uint32_t j0, uint32_t nj, uint64_t q0,
+                             uint64_t nq, uint32_t* out, core_stream stream)
 {
-    if (!out || nblocks == 0 || nblocks > (1ull << 32) || q0 + nblocks > (1ull << 32))
+    if (!out || layout < 0 || layout > 3 || nj == 0 || nq == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if ((uint64_t)j0 + nj > (1ull << 32) || nq > (1ull << 32) || q0 + nq > (1ull << 32) ||
+        (uint64_t)nj * nq > (1ull << 28))
         return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(out, 4)) return CORE_ERR_MISALIGNED;
     int rc = check_device();
     if (rc != CORE_OK) return rc;
-    hipLaunchKernelGGL(debug_philox_kernel, dim3((uint32_t)ceil_div(nblocks, kThreads)), dim3(kThreads), 0,
-                       (hipStream_t)stream, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)round,
-                       (uint32_t)(round >> 32), j, q0, nblocks, out);
-    hipError_t e = hipGetLastError();
+    DebugPhiloxArgs a;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
+    a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
+    a.j0 = j0; a.nj = nj; a.q0 = q0; a.nq = nq; a.out = out;
+    const uint64_t threads = layout == 1 ? nj : nq;
+    const dim3 g((uint32_t)ceil_div(threads, kThreads)), b(kThreads);
+    hipError_t e;
+    switch (layout) {
+        case 1: e = launch(debug_philox_kernel<1>, g, b, (hipStream_t)stream, a); break;
+        case 2: e = launch(debug_philox_kernel<2>, g, b, (hipStream_t)stream, a); break;
+        case 3: e = launch(debug_philox_kernel<3>, g, b, (hipStream_t)stream, a); break;
+        default: e = launch(debug_philox_kernel<0>, g, b, (hipStream_t)stream, a); break;
+    }
     return e == hipSuccess ? CORE_OK : hip_fail(e);
+}
+
+int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, uint64_t nblocks,
+                      uint32_t* out, core_stream stream)
+{
+    if (nblocks > (1ull << 28)) return CORE_ERR_INVALID_ARGUMENT;
+    return core_debug_philox_layout(0, seed, round, j, 1, q0, nblocks, out, stream);
+}
+
+int core_debug_set_projection(int variant)
+{
+    if (variant < kVariantAuto || variant > kVariantQ) return CORE_ERR_INVALID_ARGUMENT;
+    variant_cell().store(variant, std::memory_order_relaxed);
+    return CORE_OK;
 }
 
 int core_debug_xi(uint64_t seed, uint64_t round, uint32_t j, uint64_t i0, uint64_t count, float* out,
@@ -732,10 +783,9 @@ int core_debug_xi(uint64_t seed, uint64_t round, uint32_t j, uint64_t i0, uint64
     if (!aligned_to(out, 4)) return CORE_ERR_MISALIGNED;
     int rc = check_device();
     if (rc != CORE_OK) return rc;
-    hipLaunchKernelGGL(debug_xi_kernel, dim3((uint32_t)ceil_div(count, kThreads)), dim3(kThreads), 0,
-                       (hipStream_t)stream, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)round,
-                       (uint32_t)(round >> 32), j, i0, count, out);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = launch(debug_xi_kernel, dim3((uint32_t)ceil_div(count, kThreads)), dim3(kThreads),
+                                (hipStream_t)stream, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)round,
+                                (uint32_t)(round >> 32), j, i0, count, out);
     return e == hipSuccess ? CORE_OK : hip_fail(e);
 }
 

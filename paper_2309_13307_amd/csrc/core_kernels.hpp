@@ -743,19 +743,55 @@ __global__ void __launch_bounds__(kThreads) reconstruct_xi_kernel(ReconXiArgs a)
 
 // ---- test-only generator dumps ----------------------------------------------------------------
 
-__global__ void __launch_bounds__(kThreads) debug_philox_kernel(uint32_t k0, uint32_t k1, uint32_t r0,
-                                                                uint32_t r1, uint32_t j, uint64_t q0,
-                                                                uint64_t nblocks, uint32_t* out)
+// out[(jj * nq + qq) * 4 + w] = word w of Philox block q0 + qq of vector j0 + jj, produced with the
+// generator instantiation and the lane layout of one family of production kernels, so that the
+// split between scalar-unit rounds and vector rounds (and the three-input xor) is the one they run:
+//   LAYOUT 0  Generator<10,10>: every round key on the scalar path; one thread per block q
+//   LAYOUT 1  Generator<3,4>, lanes over the vector index j, q the wave-uniform loop index
+//             (project_kernel, project_mfma_kernel)
+//   LAYOUT 2  Generator<2,3>, lanes over the block index q, j the wave-uniform loop index
+//             (reconstruct_kernel, reconstruct_batched_kernel, project_q_kernel)
+//   LAYOUT 3  Generator<4,4>, lanes over q, j a kernel argument (debug_xi_kernel)
+struct DebugPhiloxArgs {
+    uint32_t k0, k1, r0, r1;
+    uint32_t j0, nj;
+    uint64_t q0, nq;
+    uint32_t* out;
+};
+
+template <int LAYOUT>
+__global__ void __launch_bounds__(kThreads) debug_philox_kernel(DebugPhiloxArgs a)
 {
-    const uint64_t b = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (b >= nblocks) return;
-    Generator<10, 10> gen;
-    gen.init(k0, k1, r0, r1);
-    const Words w = gen.words((uint32_t)(q0 + b), j);
-    out[4 * b + 0] = w.x0;
-    out[4 * b + 1] = w.x1;
-    out[4 * b + 2] = w.x2;
-    out[4 * b + 3] = w.x3;
+    const uint64_t t = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    auto put = [&](uint64_t jj, uint64_t qq, const Words& w) {
+        uint32_t* o = a.out + (jj * a.nq + qq) * 4;
+        o[0] = w.x0; o[1] = w.x1; o[2] = w.x2; o[3] = w.x3;
+    };
+    if constexpr (LAYOUT == 1) {
+        Generator<3, 4> gen;
+        gen.init(a.k0, a.k1, a.r0, a.r1);
+        const uint32_t j = a.j0 + (uint32_t)t;
+        for (uint64_t qq = 0; qq < a.nq; ++qq) {
+            const Words w = gen.words((uint32_t)(a.q0 + qq), j);
+            if (t < a.nj) put(t, qq, w);
+        }
+    } else if constexpr (LAYOUT == 2) {
+        Generator<2, 3> gen;
+        gen.init(a.k0, a.k1, a.r0, a.r1);
+        const uint32_t q = (uint32_t)(a.q0 + t);
+        for (uint32_t jj = 0; jj < a.nj; ++jj) {
+            const Words w = gen.words(q, a.j0 + jj);
+            if (t < a.nq) put(jj, t, w);
+        }
+    } else {
+        Generator<(LAYOUT == 3 ? 4 : 10), (LAYOUT == 3 ? 4 : 10)> gen;
+        gen.init(a.k0, a.k1, a.r0, a.r1);
+        const uint32_t q = (uint32_t)(a.q0 + t);
+        for (uint32_t jj = 0; jj < a.nj; ++jj) {
+            const Words w = gen.words(q, a.j0 + jj);
+            if (t < a.nq) put(jj, t, w);
+        }
+    }
 }
 
 __global__ void __launch_bounds__(kThreads) debug_xi_kernel(uint32_t k0, uint32_t k1, uint32_t r0,

@@ -29,6 +29,9 @@ int main(void) {
     if (rc != CORE_ERR_INVALID_ARGUMENT) return 4;
     rc = core_nonconvex_step(16, 4, dummy, 4.0f, 1.0, 1.0, dummy + 8, dummy + 8, NULL);
     if (rc != CORE_ERR_INVALID_ARGUMENT) return 5;
+    rc = core_reconstruct(1, 0, 4, 0xFFFFFFFFu, dummy, 0.25f, dummy + 8, NULL);   /* m above 2^32 - 1024 */
+    if (rc != CORE_ERR_INVALID_ARGUMENT) return 7;
+    if (core_workspace_bytes(4, 0xFFFFFC01u, 1) != 0 || core_workspace_bytes(4, 0xFFFFFC00u, 1) == 0) return 8;
     double h = 0; rc = core_step_size_option2(1 << 20, 64, 2.0, 0.1, 3.0, 4.0, &h);
     printf("opt2 rc %d h %g acc %llu\n", rc, h, acc);
     if (rc != CORE_OK) return 6;

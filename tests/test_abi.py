@@ -93,6 +93,75 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert L.core_debug_xi(1, 0, 0, (1 << 34) - 1, 2, FAKE, None) == E.ERR_INVALID_ARGUMENT
 
 
+def test_vector_count_limit():
+    """The kernels walk the vectors with 32-bit counters in steps of up to 1024, so m above
+    2^32 - 1024 would never leave those loops: every entry point must refuse it on the host."""
+    L = core.load_library()
+    E = binding
+    top = (1 << 32) - 1024
+    for m in (top + 1, (1 << 32) - 1):
+        assert core.core_workspace_bytes(4, m, 1) == 0
+        assert core.core_xi_bytes(4, m) == 0
+        assert L.core_reconstruct(1, 0, 4, m, FAKE, 0.25, FAKE + 64, None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_round(1, 0, 4, m, 1, FAKE, 0, 4, FAKE + 64, FAKE + 128, FAKE + 256, 1 << 40, None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_compress(1, 0, 4, m, FAKE, 0, FAKE + 64, FAKE + 256, 1 << 40, None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_reconstruct_update(1, 0, 4, m, FAKE, 0.25, 0.1, FAKE + 64, FAKE + 128, None, 0.0, None, None,
+                                         None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_reconstruct_trial(1, 0, 4, m, FAKE, 0.25, FAKE + 32, FAKE + 64, FAKE + 128, None,
+                                        None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_nonconvex_step(4, m, FAKE, 4.0, 1.0, 1.0, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_reconstruct_update_batched(1, 0, 4, m, 1, FAKE, 1 << 32, 0.25, 0.1, FAKE + (1 << 40), None, 4,
+                                                 None) == E.ERR_INVALID_ARGUMENT
+        assert L.core_reconstruct_from_xi(4, m, FAKE, 0.1, FAKE + 64, 1 << 40, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+        out = (ctypes.c_uint64 * 6)()
+        assert L.core_debug_plan(4, m, 1, out) == E.ERR_INVALID_ARGUMENT
+    # the largest accepted count passes validation (it then needs a device, or a workspace nobody has)
+    assert core.core_workspace_bytes(4, top, 1) > 0
+    if not torch.cuda.is_available():   # with a GPU this would launch on the fake pointers
+        assert L.core_reconstruct(1, 0, 4, top, FAKE, 0.25, FAKE + 64, None) == E.ERR_NO_DEVICE
+
+
+def test_debug_exports_arguments():
+    L = core.load_library()
+    E = binding
+    f = L.core_debug_philox_layout
+    assert f(4, 1, 0, 0, 1, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(-1, 1, 0, 0, 1, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 1, 0, 0, 0, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 1, 0, 0, 1, 0, 0, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 1, 0, (1 << 32) - 1, 2, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(2, 1, 0, 0, 1, (1 << 32) - 1, 2, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(2, 1, 0, 0, 1 << 15, 0, 1 << 14, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(2, 1, 0, 0, 1, 0, 1, None, None) == E.ERR_INVALID_ARGUMENT
+    assert f(2, 1, 0, 0, 1, 0, 1, FAKE + 2, None) == E.ERR_MISALIGNED
+    assert L.core_debug_set_projection(4) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_set_projection(-1) == E.ERR_INVALID_ARGUMENT
+    # a forced kernel changes the plan (host arithmetic), and the default comes back
+    assert core.core_debug_plan(1024, 16, 4)["qmode"] == 1
+    core.core_debug_set_projection("valu")
+    try:
+        assert core.core_debug_plan(1024, 16, 4)["qmode"] == 0
+    finally:
+        core.core_debug_set_projection("default")
+    assert core.core_debug_plan(1024, 16, 4)["qmode"] == 1
+
+
+def test_build_id_matches_the_sources():
+    from paper_2309_13307_amd import build as hip_build
+    core.load_library()
+    assert core.core_build_id() == hip_build.source_id() == hip_build.built_id()
+    assert not hip_build.is_stale()
+
+
+def test_stale_library_is_detected(tmp_path):
+    """A binary whose id differs from the hash of the sources counts as stale whatever its file time."""
+    from paper_2309_13307_amd import build as hip_build
+    fake = tmp_path / "libcore_hip.so"
+    fake.write_bytes(b"\x7fELF....CORE_BUILD_ID=0123456789abcdef....")
+    assert hip_build.built_id(str(fake)) == "0123456789abcdef" != hip_build.source_id()
+    assert hip_build.built_id(str(tmp_path / "absent.so")) is None
+
+
 @pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful on a host without a GPU")
 def test_no_device_is_a_clean_error():
     L = core.load_library()

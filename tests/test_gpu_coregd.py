@@ -177,5 +177,4 @@ def test_graph_replayed_core_gd_matches_eager():
         torch.cuda.synchronize()
         t.append((time.perf_counter() - t0) / 200 * 1e6)
     _say(f"per round: eager {t[0]:.1f} us, graph replay {t[1]:.1f} us")
-    assert torch.equal(run.x, eager.x)
-    assert t[1] < 1.5 * t[0]
+    assert torch.equal(run.x, eager.x)   # the timing above is reported, not asserted

@@ -7,7 +7,9 @@ coordinate over all m exactly.  Sampled outputs are compared element by element:
   - gtilde[i] on sampled 4-coordinate blocks against the oracle fed the GPU's pbar.
 Properties that hold at any size (reproducibility, fresh rounds) are checked on the whole output.
 """
+import os
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -34,12 +36,24 @@ def _need_gpu():
     core.load_library()
 
 
-def _sampled_check(case, rnd, pbar, gtilde, jidx, nblocks_sampled, what):
+def _oracle_columns(seed, rnd, G_host, jidx):
+    """oracle.compress for the sampled vectors, one vector per call, the calls spread over host
+    threads (the C routine runs without the interpreter lock; the oracle itself is unchanged)."""
+    workers = max(1, min(16, len(os.sched_getaffinity(0)), len(jidx)))
+    oracle.lib()
+    with ThreadPoolExecutor(workers) as pool:
+        cols = list(pool.map(lambda j: oracle.compress(seed, rnd, G_host, jidx=np.array([j], dtype=np.uint32)), jidx))
+    return np.concatenate(cols, axis=1)
+
+
+def _sampled_check(case, rnd, pbar, gtilde, jidx, nblocks_sampled, what, G_host=None):
     d, m, n = case.d, case.m, case.n
-    G_host = workloads.to_host(case.G)
-    norms = parity.row_norms(G_host)
+    if G_host is None:
+        G_host = workloads.to_host(case.G)
+    # row norms only scale the tolerance; formed on the device, one row at a time, in fp64
+    norms = np.array([float(torch.linalg.vector_norm(case.G[c].double())) for c in range(n)])
     # projections: oracle column sums over the full d for the sampled vectors
-    P_ref = oracle.compress(case.seed, rnd, G_host, jidx=jidx)
+    P_ref = _oracle_columns(case.seed, rnd, G_host, jidx)
     pbar_ref = P_ref.mean(axis=0)
     pbar_gpu = pbar.cpu().numpy().astype(np.float64)
     parity.check_projections(pbar_gpu[jidx][None, :], pbar_ref[None, :], np.array([norms.mean()]), d, m, what + " pbar")
@@ -76,13 +90,19 @@ def test_config4_full_size_sampled():
     assert 0.8 < ratio < 1.25, ratio
 
 
-@pytest.mark.timeout(400)
+@pytest.mark.timeout(900)
 def test_config5_full_size_sampled():
     case = workloads.config5(DEV)
     ws = core.alloc_workspace(case.d, case.m, case.n)
     pbar = torch.empty(case.m, dtype=torch.float32, device=DEV)
     gtilde = torch.empty(case.d, dtype=torch.float32, device=DEV)
     prev = None
+    G_host = workloads.to_host(case.G)
+    # 16 vectors over the full d and 4096 coordinate blocks over all m, in the first and the last round
+    sampled = {0: np.array([0, 1, 63, 64, 255, 256, 1023, 1024, 2047, 2049, 3000, 3071, 3072, 4000, 4094, 4095],
+                           dtype=np.uint32),
+               4: np.array([2, 65, 100, 257, 511, 512, 777, 1500, 2048, 2500, 3333, 3583, 3584, 3840, 4032, 4093],
+                           dtype=np.uint32)}
     for rnd in case.rounds:
         _say(f"config5 d={case.d} m={case.m} n={case.n} bf16, round {rnd}")
         core.core_round(case.seed, rnd, case.G, case.m, pbar=pbar, gtilde=gtilde, ws=ws)
@@ -91,9 +111,9 @@ def test_config5_full_size_sampled():
         if prev is not None:
             assert not torch.equal(prev, pbar), "rounds must use fresh vectors"
         prev = pbar.clone()
-        if rnd in (0, 4):
-            jidx = np.array([0, 2049, 4095], dtype=np.uint32) if rnd == 0 else np.array([1, 3000], dtype=np.uint32)
-            _sampled_check(case, rnd, pbar, gtilde, jidx, 1024, f"config5 round {rnd}")
+        if rnd in sampled:
+            _sampled_check(case, rnd, pbar, gtilde, sampled[rnd], 4096, f"config5 round {rnd}", G_host=G_host)
+            _say(f"config5 round {rnd}: 16 sampled vectors and 4096 sampled blocks agree with the oracle")
     # round 4 computed after rounds 0..3 equals round 4 computed cold
     pb_cold, gt_cold = core.core_round(case.seed, 4, case.G, case.m, ws=ws)
     torch.cuda.synchronize()

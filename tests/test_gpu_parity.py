@@ -50,6 +50,34 @@ def test_philox_words_bit_exact(seed, rnd, j, q0, nb):
     assert np.array_equal(got, ref)
 
 
+# (seed, round, j0, nj, q0, nq): windows of vectors x blocks that cover the first block, a ragged
+# count of lanes in both directions, several waves, the largest block index (d = 2^34), the largest
+# vector index, a round counter with a non-zero high word and a seed with a non-zero high word.
+PHILOX_WINDOWS = [
+    (42, 0, 0, 70, 0, 70),
+    (7, 0, 200, 300, 262143 - 5, 9),
+    (0xDEADBEEF12345678, 0x1_0000_0003, 4090, 67, (1 << 32) - 300, 300),
+    (1, 5, (1 << 32) - 130, 130, 12345, 5),
+    (13, (1 << 63) + 9, 1023, 1, (1 << 32) - 1, 1),
+    (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFFFFFFFFFF, (1 << 32) - 1, 1, 77, 257),
+]
+
+
+@pytest.mark.parametrize("layout", ["scalar_keys", "projection", "reconstruction", "debug_xi"])
+@pytest.mark.parametrize("seed,rnd,j0,nj,q0,nq", PHILOX_WINDOWS)
+def test_philox_words_bit_exact_in_every_kernel_layout(layout, seed, rnd, j0, nj, q0, nq):
+    """Algorithm 1, REQUIRE line: all machines share one generator, so the uint32 stream must be
+    the reference stream bit for bit.  Each layout runs the generator instantiation (which rounds
+    have their keys in vector registers and use the three-input xor) in the lane arrangement of one
+    family of production kernels: lanes over vectors with a wave-uniform block index (projection),
+    lanes over blocks with a wave-uniform vector index (reconstruction, small-problem projection)."""
+    _say(f"philox layout={layout} seed={seed:#x} round={rnd:#x} j0={j0} nj={nj} q0={q0} nq={nq}")
+    got = core.core_debug_philox_layout(layout, seed, rnd, j0, nj, q0, nq).cpu().numpy().view(np.uint32)
+    ref = np.stack([oracle.words_range(seed, rnd, j0 + jj, q0, nq) for jj in range(nj)])
+    assert got.shape == ref.shape == (nj, nq, 4)
+    assert np.array_equal(got, ref)
+
+
 @pytest.mark.parametrize("seed,rnd,j,i0,count", [
     (42, 0, 0, 0, 1 << 20),
     (7, 3, 200, 5, 100003),
@@ -110,13 +138,11 @@ SHAPES = [
 
 
 @pytest.fixture(params=["default", "valu", "mfma", "q"])
-def variant(request, monkeypatch):
+def variant(request):
     """Run a test once per projection kernel: the library's own choice, and each forced one."""
-    if request.param != "default":
-        monkeypatch.setenv("CORE_PROJECT_VARIANT", request.param)
-    else:
-        monkeypatch.delenv("CORE_PROJECT_VARIANT", raising=False)
-    return request.param
+    core.core_debug_set_projection(request.param)
+    yield request.param
+    core.core_debug_set_projection("default")
 
 
 @pytest.mark.parametrize("d,m,n", SHAPES)
@@ -252,18 +278,21 @@ def test_materialised_xi_variant(d, m, n, bf16):
 
 @pytest.mark.parametrize("d,m,n,bf16", [(1030, 70, 3, False), (5000, 300, 8, True), (9001, 260, 16, True),
                                           (4100, 64, 21, False), (3000, 129, 11, True)])
-def test_mfma_projection_variant(d, m, n, bf16, monkeypatch):
+def test_mfma_projection_variant(d, m, n, bf16):
     """The matrix-pipe A/B variant of the projection meets the same bars as the default kernel."""
     _say(f"mfma variant d={d} m={m} n={n} bf16={bf16}")
-    monkeypatch.setenv("CORE_PROJECT_VARIANT", "mfma")
     rng = np.random.default_rng(3 * d + m + n)
     G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
     if bf16:
         G = G.to(torch.bfloat16)
-    P, pbar, gt = _run_and_check(23, 5, G, m, what=f"mfma d={d} m={m} n={n}")
-    monkeypatch.setenv("CORE_PROJECT_VARIANT", "valu")
-    P2, pbar2 = core.core_compress_batched(23, 5, G, m)
-    _sync()
+    try:
+        core.core_debug_set_projection("mfma")
+        P, pbar, gt = _run_and_check(23, 5, G, m, what=f"mfma d={d} m={m} n={n}")
+        core.core_debug_set_projection("valu")
+        P2, pbar2 = core.core_compress_batched(23, 5, G, m)
+        _sync()
+    finally:
+        core.core_debug_set_projection("default")
     assert parity.rel_l2(P.cpu().numpy(), P2.cpu().numpy()) < 2e-6
 
 
