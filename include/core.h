@@ -73,7 +73,8 @@ enum {
     CORE_ERR_MISALIGNED = -2,         /* pointer not aligned to its element size */
     CORE_ERR_WORKSPACE_TOO_SMALL = -3,/* ws_bytes < core_workspace_bytes(d, m, n) */
     CORE_ERR_HIP = -4,                /* the HIP runtime refused a launch (see core_last_hip_error) */
-    CORE_ERR_NO_DEVICE = -5           /* no usable GPU in this process */
+    CORE_ERR_NO_DEVICE = -5,          /* no usable GPU in this process */
+    CORE_ERR_STATIC_SCRATCH_TOO_SMALL = -6 /* core_round_static: sizes need more than CORE_STATIC_SCRATCH_BYTES */
 };
 
 /* Static, human-readable text for a return code. */
@@ -127,6 +128,26 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
                const void *G, core_dtype dt, uint64_t ld,
                float *pbar, float *gtilde,
                void *ws, size_t ws_bytes, core_stream stream);
+
+/* core_round for callers that cannot allocate device memory or supply a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results as core_round, but the scratch (per-chunk partial projections
+ * and the staged cross-chunk sums) lives in a fixed array inside the library, of
+ * CORE_STATIC_SCRATCH_BYTES per GPU, which each GPU the library runs on holds until the process
+ * ends.  The call allocates and frees nothing; the first call on a device looks up that device's
+ * copy of the array (the device current on the calling thread must be the stream's device).
+ *   - Sizes with core_workspace_bytes(d, m, n) > CORE_STATIC_SCRATCH_BYTES are refused with
+ *     CORE_ERR_STATIC_SCRATCH_TOO_SMALL before anything is launched (the ResNet-50-sized case,
+ *     d = 25,557,032, m = 1024, n = 8, needs 68 MB and fits).
+ *   - All calls on one GPU share the one array: calls that may overlap in time on the same GPU
+ *     (different streams, or different host threads) race on it and must be serialised by the
+ *     caller; use core_round with separate workspaces for concurrent rounds.
+ *   - The array keeps the previous call's contents.  Nothing needs clearing: every partial sum is
+ *     written by the call's own projection kernels before its reduction kernels read it. */
+#define CORE_STATIC_SCRATCH_BYTES (80u << 20)
+int core_round_static(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n,
+                      const void *G, core_dtype dt, uint64_t ld,
+                      float *pbar, float *gtilde, core_stream stream);
 
 /* ---- reconstruction fused with the optimiser step -------------------------------------------
  * Algorithm 2 ends each round with x^{k+1} = x^k - h_k * gtilde; CORE-AGD (appendix, heavy-ball

@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     core_nonconvex_step, core_step_size_option2, core_reconstruct_trial, core_round_trial,
     core_accept_trial, core_debug_plan, core_round_update_r, core_advance_round, core_round_trial_r,
     core_reconstruct_update_batched, core_build_id, core_debug_philox_layout, core_debug_set_projection,
+    core_round_static,
 )

@@ -22,6 +22,8 @@ ERR_MISALIGNED = -2
 ERR_WORKSPACE_TOO_SMALL = -3
 ERR_HIP = -4
 ERR_NO_DEVICE = -5
+ERR_STATIC_SCRATCH_TOO_SMALL = -6
+STATIC_SCRATCH_BYTES = 80 << 20
 
 EXPORTS = (
     "core_strerror", "core_last_hip_error", "core_workspace_bytes", "core_compress",
@@ -31,7 +33,7 @@ EXPORTS = (
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
     "core_accept_trial", "core_debug_plan", "core_round_update_r", "core_advance_round",
     "core_round_trial_r", "core_reconstruct_update_batched", "core_build_id",
-    "core_debug_philox_layout", "core_debug_set_projection",
+    "core_debug_philox_layout", "core_debug_set_projection", "core_round_static",
 )
 
 
@@ -74,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     L.core_reconstruct.restype = i32
     L.core_round.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz, vp]
     L.core_round.restype = i32
+    L.core_round_static.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp]
+    L.core_round_static.restype = i32
     L.core_xi_bytes.argtypes = [u64, u32]
     L.core_xi_bytes.restype = sz
     L.core_compress_batched_store_xi.argtypes = [u64, u64, u64, u32, u32, vp, i32, u64, vp, vp, vp, sz,
@@ -240,6 +244,21 @@ def core_round(seed: int, rnd: int, G: torch.Tensor, m: int, d: int | None = Non
                                    _stream())
     _check(rc, "core_round")
     return pbar, gtilde
+
+
+def core_round_static(seed: int, rnd: int, G: torch.Tensor, m: int, pbar: torch.Tensor, gtilde: torch.Tensor,
+                      d: int | None = None) -> None:
+    """core_round with the scratch in the library's fixed array: the call allocates nothing, so
+    both outputs must be supplied."""
+    _require_cuda(G, pbar, gtilde)
+    if G.dim() != 2 or G.stride(1) != 1:
+        raise ValueError("G must be 2-D with unit stride along the coordinate axis")
+    n, ld = G.shape[0], G.stride(0)
+    if d is None:
+        d = G.shape[1]
+    rc = load_library().core_round_static(seed, rnd, d, m, n, G.data_ptr(), _dtype_code(G), ld,
+                                          pbar.data_ptr(), gtilde.data_ptr(), _stream())
+    _check(rc, "core_round_static")
 
 
 def _ptr(t):

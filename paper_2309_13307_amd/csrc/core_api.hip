@@ -6,6 +6,7 @@
 #include <string.h>
 #include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "../../include/core.h"
 #include "core_kernels.hpp"
@@ -423,6 +424,35 @@ size_t xi_bytes(uint64_t d, uint32_t m)
     return (size_t)(nblk * m * 16);
 }
 
+// ---- fixed scratch for callers that cannot allocate ---------------------------------------------
+// core_round_static runs core_round with its workspace in this array instead of caller memory.
+// Every GPU the library runs on holds its own copy until the process ends.  In host code the
+// array's name is only a handle for the runtime's symbol lookup: the device address is asked for
+// once per device and that address is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[CORE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return CORE_ERR_INVALID_ARGUMENT;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // address of this device's copy
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CORE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -438,6 +468,8 @@ const char* core_strerror(int code)
         case CORE_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than core_workspace_bytes(d, m, n)";
         case CORE_ERR_HIP: return "HIP runtime error on launch (see core_last_hip_error)";
         case CORE_ERR_NO_DEVICE: return "no usable GPU device";
+        case CORE_ERR_STATIC_SCRATCH_TOO_SMALL:
+            return "sizes need more scratch than the library's fixed CORE_STATIC_SCRATCH_BYTES; use core_round with a caller workspace";
         default: return "unknown error code";
     }
 }
@@ -482,6 +514,26 @@ int core_round(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n
     if (rc != CORE_OK) return rc;
     if ((rc = validate_reconstruct(d, m, pbar, gtilde)) != CORE_OK) return rc;
     if ((rc = check_device()) != CORE_OK) return rc;
+    rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
+    if (rc != CORE_OK) return rc;
+    return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream);
+}
+
+int core_round_static(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint32_t n, const void* G,
+                      core_dtype dt, uint64_t ld, float* pbar, float* gtilde, core_stream stream)
+{
+    const size_t need = workspace_bytes(d, m, n);
+    if (need == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (need > (size_t)CORE_STATIC_SCRATCH_BYTES) return CORE_ERR_STATIC_SCRATCH_TOO_SMALL;
+    // validation needs a non-null, aligned workspace pointer; the real one is looked up only
+    // after every argument has passed
+    Plan plan;
+    int rc = validate_compress(d, m, n, G, dt, ld, nullptr, pbar, (const void*)(uintptr_t)256, need, plan);
+    if (rc != CORE_OK) return rc;
+    if ((rc = validate_reconstruct(d, m, pbar, gtilde)) != CORE_OK) return rc;
+    if ((rc = check_device()) != CORE_OK) return rc;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != CORE_OK) return rc;
     rc = enqueue_compress(seed, round, d, m, n, G, dt, ld, nullptr, pbar, ws, plan, (hipStream_t)stream);
     if (rc != CORE_OK) return rc;
     return enqueue_reconstruct(seed, round, d, m, pbar, 1.0f / (float)m, gtilde, (hipStream_t)stream);

@@ -30,11 +30,11 @@ def test_library_exports_every_declared_symbol():
 
 def test_strerror_covers_all_codes():
     seen = set()
-    for code in (0, -1, -2, -3, -4, -5):
+    for code in (0, -1, -2, -3, -4, -5, -6):
         s = core.strerror(code)
         assert s and s != core.strerror(-99)
         seen.add(s)
-    assert len(seen) == 6
+    assert len(seen) == 7
 
 
 def test_workspace_bytes():
@@ -119,6 +119,27 @@ def test_vector_count_limit():
     assert core.core_workspace_bytes(4, top, 1) > 0
     if not torch.cuda.is_available():   # with a GPU this would launch on the fake pointers
         assert L.core_reconstruct(1, 0, 4, top, FAKE, 0.25, FAKE + 64, None) == E.ERR_NO_DEVICE
+
+
+def test_static_scratch_entry_point_arguments():
+    L = core.load_library()
+    E = binding
+    f = L.core_round_static
+    # sizes that need more than the fixed array are refused, whatever else is passed
+    assert core.core_workspace_bytes(124_439_808, 4096, 16) > E.STATIC_SCRATCH_BYTES
+    assert f(1, 0, 124_439_808, 4096, 16, FAKE, 1, 124_439_808, FAKE + 64, FAKE + 128, None) == E.ERR_STATIC_SCRATCH_TOO_SMALL
+    assert 0 < core.core_workspace_bytes(25_557_032, 1024, 8) <= E.STATIC_SCRATCH_BYTES
+    assert f(1, 0, 0, 16, 4, FAKE, 0, 1024, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, None, 0, 1024, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, FAKE, 0, 1024, None, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE + 64, None, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, FAKE, 0, 1000, FAKE + 64, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
+    assert f(1, 0, 1024, 16, 4, FAKE + 2, 0, 1024, FAKE + 64, FAKE + 128, None) == E.ERR_MISALIGNED
+    assert "CORE_STATIC_SCRATCH_BYTES" in core.strerror(E.ERR_STATIC_SCRATCH_TOO_SMALL)
+    text = open(os.path.join(ROOT, "include", "core.h")).read()
+    assert re.search(r"#define\s+CORE_STATIC_SCRATCH_BYTES\s+\(80u << 20\)", text) and E.STATIC_SCRATCH_BYTES == 80 << 20
+    if not torch.cuda.is_available():
+        assert f(1, 0, 1024, 16, 4, FAKE, 0, 1024, FAKE + 64, FAKE + 128, None) == E.ERR_NO_DEVICE
 
 
 def test_debug_exports_arguments():
