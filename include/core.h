@@ -317,9 +317,13 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
 
 /* The launch plan core_compress_batched / core_round would use for these sizes (host arithmetic,
  * nothing is launched; `plan` is a HOST pointer):
- *   plan[0] 1 = lanes-over-coordinates projection (few vectors or little work), 0 = lanes-over-vectors
- *   plan[1] vector tiles (256 vectors each; groups of 4 vectors in mode 1)
- *   plan[2] chunks of d            plan[3] tiles per chunk (256 coordinates each; 1024 in mode 1)
+ *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (few vectors or
+ *           little work), 2 = one workgroup per vector with the sums finished inside it (tiny
+ *           problems with at most 8 clients and d <= 65536: projection, cross-chunk sum and client
+ *           mean are then a single launch and the workspace is not used)
+ *   plan[1] vector tiles (256 vectors each; groups of 4 vectors in mode 1; m in mode 2)
+ *   plan[2] chunks of d            plan[3] tiles per chunk (256 coordinates each; 1024 in mode 1;
+ *                                          Philox blocks per thread in mode 2)
  *   plan[4] slices of the cross-chunk sum
  *   plan[5] projection blocks launched per pass of clients
  * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */
@@ -345,8 +349,9 @@ int core_debug_philox_layout(int layout, uint64_t seed, uint64_t round, uint32_t
 
 /* Force the projection kernel for every later call in this process (A/B measurements and tests
  * that drive each kernel over each shape): 0 = the library's own choice, 1 = vector-ALU kernel
- * with lanes over vectors, 2 = matrix-pipe kernel, 3 = lanes-over-coordinates kernel.  The
- * environment variable CORE_PROJECT_VARIANT = valu | mfma | q sets the initial value; it is read
+ * with lanes over vectors, 2 = matrix-pipe kernel, 3 = lanes-over-coordinates kernel, 4 = the
+ * one-launch kernel for tiny problems where its limits allow (else as 3).  The environment
+ * variable CORE_PROJECT_VARIANT = valu | mfma | q | small sets the initial value; it is read
  * once.  Not synchronised with calls in flight on other host threads. */
 int core_debug_set_projection(int variant);
 

@@ -429,7 +429,7 @@ def core_debug_plan(d: int, m: int, n: int) -> dict:
     out = (ctypes.c_uint64 * 6)()
     rc = load_library().core_debug_plan(d, m, n, out)
     _check(rc, "core_debug_plan")
-    keys = ("qmode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks")
+    keys = ("mode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks")
     return dict(zip(keys, (int(v) for v in out)))
 
 
@@ -521,7 +521,7 @@ def core_debug_philox_layout(layout: str | int, seed: int, rnd: int, j0: int, nj
     return out
 
 
-PROJECTION_VARIANTS = {"default": 0, "valu": 1, "mfma": 2, "q": 3}
+PROJECTION_VARIANTS = {"default": 0, "valu": 1, "mfma": 2, "q": 3, "small": 4}
 
 
 def core_debug_set_projection(variant: str | int) -> None:

@@ -37,15 +37,27 @@ inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr uint32_t kBlockSlots = 2048;   // resident 256-thread blocks: 256 CUs x 8
+constexpr uint64_t kWaveSlots = 8192;    // resident waves at 8 per SIMD: 256 CUs x 4 SIMDs x 8
+
+// How the projection is laid out on the chip.
+enum PlanMode : int {
+    kPlanVectors = 0,   // lanes over the vectors j, blocks of 256 vectors x a chunk of 256-coordinate tiles
+    kPlanCoords = 1,    // lanes over the coordinates, blocks of kQJ vectors x a chunk of 1024-coordinate tiles
+    kPlanSmall = 2      // one workgroup per vector over the whole of d, sums finished inside it (one launch)
+};
 
 struct Plan {
-    bool qmode;            // lanes-over-q projection (few vectors or little work)
-    uint32_t jtiles;       // vector tiles (256 vectors) or, in qmode, groups of kQJ vectors
+    int mode;
+    uint32_t jtiles;       // vector tiles (256 vectors); groups of kQJ vectors (kPlanCoords); m (kPlanSmall)
     uint32_t nchunks;
     uint32_t tiles_per_chunk;
     uint32_t Z;            // slices of the cross-chunk sum
+    uint32_t small_threads;   // kPlanSmall: threads per workgroup
     size_t part_off, psum_off, total;
 };
+
+constexpr uint64_t kSmallMaxD = 65536;      // kPlanSmall: a thread's fp32 chain stays <= 256 terms
+constexpr uint32_t kSmallMaxClients = 8;
 
 constexpr uint32_t kQTilesPerChunkMax = 64;   // bounds the fp32 chains of the lanes-over-q kernel
 // A block adds one fp32 tile sum (256 terms) per tile to its fp32 chunk sum; the chunk sums are then
@@ -62,7 +74,7 @@ constexpr uint64_t kMaxGridBlocks = 0x7fffffffull;   // HIP's limit on gridDim.x
 // the tests that drive every kernel over every shape.  Set with core_debug_set_projection (a
 // test-only export); the environment variable CORE_PROJECT_VARIANT=valu|mfma|q gives the initial
 // value and is read once per process.
-enum Variant : int { kVariantAuto = 0, kVariantValu = 1, kVariantMfma = 2, kVariantQ = 3 };
+enum Variant : int { kVariantAuto = 0, kVariantValu = 1, kVariantMfma = 2, kVariantQ = 3, kVariantSmall = 4 };
 
 int variant_from_env()
 {
@@ -71,6 +83,7 @@ int variant_from_env()
     if (strcmp(v, "valu") == 0) return kVariantValu;
     if (strcmp(v, "mfma") == 0) return kVariantMfma;
     if (strcmp(v, "q") == 0) return kVariantQ;
+    if (strcmp(v, "small") == 0) return kVariantSmall;
     return kVariantAuto;
 }
 
@@ -87,10 +100,24 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
     if (d == 0 || d > kMaxD || m == 0 || m > kMaxM || n == 0 || n > kMaxN) return false;
     const uint64_t tiles_total = ceil_div(d, kTile);
     const int forced = forced_variant();
-    if (forced == kVariantQ) p.qmode = allow_qmode;
-    else if (forced == kVariantValu || forced == kVariantMfma) p.qmode = false;
-    else p.qmode = allow_qmode && (m < 64 || ceil_div(m, 64) * tiles_total <= 1024);
-    if (p.qmode) {
+    const bool small_ok = allow_qmode && n <= kSmallMaxClients && d <= kSmallMaxD && m <= 0x7fffffffu;
+    const bool little_work = m < 64 || ceil_div(m, 64) * tiles_total <= 1024;
+    const int coords_or_vectors = allow_qmode ? kPlanCoords : kPlanVectors;
+    if (forced == kVariantQ) p.mode = coords_or_vectors;
+    else if (forced == kVariantSmall) p.mode = small_ok ? kPlanSmall : coords_or_vectors;
+    else if (forced == kVariantValu || forced == kVariantMfma) p.mode = kPlanVectors;
+    else p.mode = !(allow_qmode && little_work) ? kPlanVectors : (small_ok ? kPlanSmall : kPlanCoords);
+    p.small_threads = 0;
+    if (p.mode == kPlanSmall) {
+        // one Philox block per thread where d allows it: the serial chain of a thread is what a
+        // launch-bound round waits for
+        uint64_t threads = ceil_div(ceil_div(d, 4), 64) * 64;
+        if (threads > 1024) threads = 1024;
+        p.small_threads = (uint32_t)threads;
+        p.jtiles = m;
+        p.nchunks = 1;
+        p.tiles_per_chunk = (uint32_t)ceil_div(ceil_div(d, 4), threads);
+    } else if (p.mode == kPlanCoords) {
         const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
         p.jtiles = (uint32_t)ceil_div(m, kQJ);
         uint64_t want = ceil_div(kTargetBlocks / 2, p.jtiles);
@@ -106,12 +133,15 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
         if (want < 1) want = 1;
         if (want > tiles_total) want = tiles_total;
         uint64_t tpc = ceil_div(tiles_total, want);
+#ifdef CORE_EXPERIMENT
+        if (const char* e = getenv("CORE_TPC")) tpc = strtoull(e, nullptr, 10);
+#endif
         if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
         p.tiles_per_chunk = (uint32_t)tpc;
         p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
     }
     // one block per (chunk, vector tile): the grid must stay a valid launch
-    const uint64_t grid = p.qmode ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
+    const uint64_t grid = p.mode != kPlanVectors ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
     if (grid > kMaxGridBlocks) return false;
     uint32_t Z = p.nchunks / 128u;
     if (Z < 1) Z = 1;
@@ -119,8 +149,11 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
     p.Z = Z;
     const uint64_t E = (uint64_t)n * m;
     size_t off = 0;
-    p.part_off = off;  off = align_up(off + (size_t)p.nchunks * E * sizeof(float), 256);
-    p.psum_off = off;  off = align_up(off + (size_t)Z * E * sizeof(double), 256);
+    p.part_off = p.psum_off = 0;
+    if (p.mode != kPlanSmall) {   // the one-launch plan keeps every partial sum inside its workgroups
+        p.part_off = off;  off = align_up(off + (size_t)p.nchunks * E * sizeof(float), 256);
+        p.psum_off = off;  off = align_up(off + (size_t)Z * E * sizeof(double), 256);
+    }
     p.total = off;
     return true;
 }
@@ -158,11 +191,18 @@ int check_device()
 template <typename T> struct same_type { using type = T; };
 
 template <typename... Params>
+hipError_t launch_lds(void (*kernel)(Params...), dim3 grid, dim3 block, size_t dynamic_lds, hipStream_t st,
+                      typename same_type<Params>::type... args)
+{
+    void* ptrs[] = {(void*)&args...};
+    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, dynamic_lds, st);
+}
+
+template <typename... Params>
 hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t st,
                   typename same_type<Params>::type... args)
 {
-    void* ptrs[] = {(void*)&args...};
-    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
+    return launch_lds(kernel, grid, block, 0, st, args...);
 }
 
 bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -245,7 +285,22 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     a.xi_store = xi_store;
     const bool bf16 = (dt == CORE_DTYPE_BF16);
 
-    if (plan.qmode) {
+    if (plan.mode == kPlanSmall) {
+        ProjectSmallArgs sa;
+        sa.G = G; sa.ld = ld; sa.d = d; sa.m = m; sa.n = n;
+        sa.k0 = a.k0; sa.k1 = a.k1; sa.r0 = a.r0; sa.r1 = a.r1; sa.round_dev = a.round_dev;
+        sa.vec_load = (aligned_to(G, bf16 ? 8 : 16) && ld % 4 == 0) ? 1 : 0;
+        sa.P = P; sa.pbar = pbar;
+        const dim3 g(m), b(plan.small_threads);
+        hipError_t e;
+        if (n <= 1)      e = bf16 ? launch(project_small_kernel<1, true>, g, b, st, sa) : launch(project_small_kernel<1, false>, g, b, st, sa);
+        else if (n <= 2) e = bf16 ? launch(project_small_kernel<2, true>, g, b, st, sa) : launch(project_small_kernel<2, false>, g, b, st, sa);
+        else if (n <= 4) e = bf16 ? launch(project_small_kernel<4, true>, g, b, st, sa) : launch(project_small_kernel<4, false>, g, b, st, sa);
+        else             e = bf16 ? launch(project_small_kernel<8, true>, g, b, st, sa) : launch(project_small_kernel<8, false>, g, b, st, sa);
+        return e == hipSuccess ? CORE_OK : hip_fail(e);
+    }
+
+    if (plan.mode == kPlanCoords) {
         const uint32_t blocks = plan.nchunks * plan.jtiles;
         for (uint32_t c0 = 0; c0 < n; c0 += 8) {
             const uint32_t nc = (n - c0 < 8u) ? (n - c0) : 8u;
@@ -336,9 +391,26 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     // two Philox blocks per thread share the scalar work of a vector; one per thread when that
     // would leave block slots empty (small d)
     const bool two = ceil_div(nblk, (uint64_t)kThreads * 2) >= 2 * kBlockSlots;
+    hipError_t e;
+    // short vectors: fewer 64-block columns than 4 waves per SIMD.  Split the vectors j of a
+    // column over several waves of one workgroup until there are that many (measured at 2^20
+    // coordinates, 4096 columns: one wave per column 122 us, two 129 us, four 127 us; at 4096
+    // coordinates, 16 columns: 17 us unsplit, 9 us with 16 waves per column).
+    const uint64_t columns = ceil_div(nblk, 64);
+    uint32_t split = 1;
+    while (split < (uint32_t)kSplitMaxWaves && columns * split < kWaveSlots / 2 && 2 * split <= m) split *= 2;
+#ifdef CORE_EXPERIMENT
+    if (const char* ev = getenv("CORE_SPLIT")) split = (uint32_t)strtoul(ev, nullptr, 10);
+#endif
+    if (!two && split >= 2) {
+        const dim3 g((uint32_t)columns), b(64 * split);
+        const size_t lds = (size_t)split * 4 * 64 * sizeof(float);
+        e = up ? launch_lds(reconstruct_split_kernel<true>, g, b, lds, st, a)
+               : launch_lds(reconstruct_split_kernel<false>, g, b, lds, st, a);
+        return e == hipSuccess ? CORE_OK : hip_fail(e);
+    }
     const uint32_t blocks = (uint32_t)ceil_div(nblk, (uint64_t)kThreads * (two ? 2 : 1));
     const dim3 g(blocks), b(kThreads);
-    hipError_t e;
     if (up) e = two ? launch(reconstruct_kernel<true, 2>, g, b, st, a) : launch(reconstruct_kernel<true, 1>, g, b, st, a);
     else    e = two ? launch(reconstruct_kernel<false, 2>, g, b, st, a) : launch(reconstruct_kernel<false, 1>, g, b, st, a);
     return e == hipSuccess ? CORE_OK : hip_fail(e);
@@ -779,12 +851,12 @@ int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6])
 {
     Plan p;
     if (!plan || !make_plan(d, m, n, true, p)) return CORE_ERR_INVALID_ARGUMENT;
-    plan[0] = p.qmode ? 1 : 0;
+    plan[0] = (uint64_t)p.mode;
     plan[1] = p.jtiles;
     plan[2] = p.nchunks;
     plan[3] = p.tiles_per_chunk;
     plan[4] = p.Z;
-    plan[5] = p.qmode ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
+    plan[5] = p.mode != kPlanVectors ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
     return CORE_OK;
 }
 
@@ -823,7 +895,7 @@ int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, ui
 
 int core_debug_set_projection(int variant)
 {
-    if (variant < kVariantAuto || variant > kVariantQ) return CORE_ERR_INVALID_ARGUMENT;
+    if (variant < kVariantAuto || variant > kVariantSmall) return CORE_ERR_INVALID_ARGUMENT;
     variant_cell().store(variant, std::memory_order_relaxed);
     return CORE_OK;
 }

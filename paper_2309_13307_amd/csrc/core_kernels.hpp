@@ -338,6 +338,106 @@ __global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
     }
 }
 
+// Projection, cross-chunk sum and client mean in one launch, for problems so small that launches
+// are what a round costs (a few thousand coordinates, at most 8 clients): Algorithm 2's "machine i
+// sends p_ij" and "central machine sends the combined p_j back" back to back.  One workgroup per
+// vector j walks the whole of d, lanes over the Philox block q, each thread keeping its share of the
+// NC sums; the workgroup then holds every term of P[c][j], adds them in a fixed order (butterfly
+// inside each wave, then the waves in order) and writes P[c][j] (optional) and
+// pbar[j] = (1/n) sum_c P[c][j] itself.  No partial sums leave the workgroup, so the workspace is
+// not touched.  blockDim.x is a multiple of 64, at most 1024.
+struct ProjectSmallArgs {
+    const void* G;        // [n][ld]
+    uint64_t ld;
+    uint64_t d;
+    uint32_t m;
+    uint32_t n;           // clients, n <= NC
+    uint32_t k0, k1, r0, r1;
+    const uint32_t* round_dev;
+    int vec_load;         // rows start on 16-byte (fp32) / 8-byte (bf16) boundaries: 4 coordinates per load
+    float* P;             // [n][m] or null
+    float* pbar;          // [m]
+};
+
+template <int NC, bool BF16>
+__global__ void __launch_bounds__(1024) project_small_kernel(ProjectSmallArgs a)
+{
+    __shared__ float red[16][NC];
+    const uint32_t t = threadIdx.x, nthreads = blockDim.x;
+    const uint32_t j = blockIdx.x;
+    const uint64_t nblk = (a.d + 3) / 4;
+
+    Generator<2, 3> gen;
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
+
+    float acc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
+
+    for (uint64_t q = t; q < nblk; q += nthreads) {
+        const uint64_t i = 4 * q;
+        float g[NC][4];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            g[c][0] = g[c][1] = g[c][2] = g[c][3] = 0.0f;
+            if ((uint32_t)c < a.n) {
+                const uint64_t base = (uint64_t)c * a.ld + i;
+                if (a.vec_load && i + 4 <= a.d) {
+                    if constexpr (BF16) {
+                        const uint2 v = *reinterpret_cast<const uint2*>((const uint16_t*)a.G + base);
+                        g[c][0] = __uint_as_float(v.x << 16); g[c][1] = __uint_as_float(v.x & 0xffff0000u);
+                        g[c][2] = __uint_as_float(v.y << 16); g[c][3] = __uint_as_float(v.y & 0xffff0000u);
+                    } else {
+                        const float4 v = *reinterpret_cast<const float4*>((const float*)a.G + base);
+                        g[c][0] = v.x; g[c][1] = v.y; g[c][2] = v.z; g[c][3] = v.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (i + k < a.d) g[c][k] = load_g<BF16>(a.G, base + k);
+                }
+            }
+        }
+        float z0, z1, z2, z3;
+        gen.block((uint32_t)q, j, z0, z1, z2, z3);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            acc[c] = fmaf(z0, g[c][0], acc[c]);
+            acc[c] = fmaf(z1, g[c][1], acc[c]);
+            acc[c] = fmaf(z2, g[c][2], acc[c]);
+            acc[c] = fmaf(z3, g[c][3], acc[c]);
+        }
+    }
+
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        float v = acc[c];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+        if ((t & 63u) == 0) red[t >> 6][c] = v;
+    }
+    __syncthreads();
+    // lane c of the first wave adds client c's per-wave sums in wave order; lane 0 then adds the
+    // clients in order (values fetched from the other lanes) for the mean
+    if (t < 64) {
+        const uint32_t waves = nthreads >> 6;
+        float tot = 0.0f;
+        if (t < a.n) {
+            tot = red[0][t];
+            for (uint32_t w = 1; w < waves; ++w) tot += red[w][t];
+            tot *= kXiScale;
+            if (a.P) a.P[(uint64_t)t * a.m + j] = tot;
+        }
+        double mean = 0.0;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const float v = __shfl(tot, c);
+            if ((uint32_t)c < a.n) mean += (double)v;
+        }
+        if (t == 0) a.pbar[j] = (float)(mean / (double)a.n);
+    }
+}
+
 // Cross-chunk sum (a4), stage A: psum[z][c][j] = sum over the chunks of slice z of part[k][c][j],
 // fp64, fixed order.  grid = (ceil(m/32), n, Z); block = 32 vectors x 8 interleaved sub-slices.
 // Chunk k belongs to slice k % Z and, inside it, to sub-slice (k / Z) % 8.
@@ -429,16 +529,69 @@ struct ReconArgs {
     const float* h_dev;   // when non-null, the step is read from device memory instead of h
 };
 
-// UPDATE: the reconstruction feeds the optimiser step in its epilogue instead of (or as well as)
-// writing gtilde: x_new = y - h * gtilde (last line of the loop of Algorithm 2; with y = y^k it is
-// the update of CORE-AGD), and optionally the next heavy-ball point
-// y_next = x_new + (1 - beta)(x_new - x_cur) (first line of the loop of CORE-AGD).
+// Epilogue shared by the reconstruction kernels: the four sums of Philox block q become
+// gtilde[4q..4q+3] = scale * sum (Eq. (reconstruction)) and, with UPDATE, feed the optimiser step
+// instead of (or as well as) being written: x_new = y - h * gtilde (last line of the loop of
+// Algorithm 2; with y = y^k it is the update of CORE-AGD), and optionally the next heavy-ball
+// point y_next = x_new + (1 - beta)(x_new - x_cur) (first line of the loop of CORE-AGD).
+template <bool UPDATE>
+__device__ __forceinline__ void finish_block(const ReconArgs& a, uint64_t q, const float (&sum)[4])
+{
+    const uint64_t nblk = (a.d + 3) / 4;   // Philox blocks in the vector
+    if (q >= nblk) return;
+    const uint64_t i = 4 * q;
+    const float sc = a.scale * kXiScale;
+    float v[4] = {sc * sum[0], sc * sum[1], sc * sum[2], sc * sum[3]};
+    const bool full = a.vec_store && i + 4 <= a.d;
+    if (a.gtilde) {
+        if (full) {
+            *reinterpret_cast<float4*>(a.gtilde + i) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) if (i + k < a.d) a.gtilde[i + k] = v[k];
+        }
+    }
+    if constexpr (UPDATE) {
+        float yv[4] = {0.f, 0.f, 0.f, 0.f}, xc[4] = {0.f, 0.f, 0.f, 0.f};
+        if (full) {
+            const float4 t4 = *reinterpret_cast<const float4*>(a.y + i);
+            yv[0] = t4.x; yv[1] = t4.y; yv[2] = t4.z; yv[3] = t4.w;
+            if (a.y_next) {
+                const float4 c4 = *reinterpret_cast<const float4*>(a.x_cur + i);
+                xc[0] = c4.x; xc[1] = c4.y; xc[2] = c4.z; xc[3] = c4.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) if (i + k < a.d) {
+                yv[k] = a.y[i + k];
+                if (a.y_next) xc[k] = a.x_cur[i + k];
+            }
+        }
+        const float h = a.h_dev ? *a.h_dev : a.h;
+        float xn[4], yn[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            xn[k] = fmaf(-h, v[k], yv[k]);
+            yn[k] = fmaf(a.omb, xn[k] - xc[k], xn[k]);
+        }
+        if (full) {
+            *reinterpret_cast<float4*>(a.x_new + i) = make_float4(xn[0], xn[1], xn[2], xn[3]);
+            if (a.y_next) *reinterpret_cast<float4*>(a.y_next + i) = make_float4(yn[0], yn[1], yn[2], yn[3]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) if (i + k < a.d) {
+                a.x_new[i + k] = xn[k];
+                if (a.y_next) a.y_next[i + k] = yn[k];
+            }
+        }
+    }
+}
+
 template <bool UPDATE, int kReconBlocks>
 __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
 {
     __shared__ float pb[kPbarTile];
     const uint32_t t = threadIdx.x;
-    const uint64_t nblk = (a.d + 3) / 4;   // Philox blocks in the vector
     const uint64_t qbase = (uint64_t)blockIdx.x * (kThreads * kReconBlocks) + t;
 
     // lanes differ in q (counter word 0) only: the state is fully divergent after 2-3 rounds
@@ -489,56 +642,63 @@ __global__ void __launch_bounds__(kThreads) reconstruct_kernel(ReconArgs a)
     }
 
 #pragma unroll
-    for (int r = 0; r < kReconBlocks; ++r) {
-        const uint64_t q = qbase + (uint64_t)r * kThreads;
-        if (q >= nblk) continue;
-        const uint64_t i = 4 * q;
-        const float sc = a.scale * kXiScale;
-        float v[4] = {sc * outer[r][0], sc * outer[r][1], sc * outer[r][2], sc * outer[r][3]};
-        const bool full = a.vec_store && i + 4 <= a.d;
-        if (a.gtilde) {
-            if (full) {
-                *reinterpret_cast<float4*>(a.gtilde + i) = make_float4(v[0], v[1], v[2], v[3]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) if (i + k < a.d) a.gtilde[i + k] = v[k];
-            }
+    for (int r = 0; r < kReconBlocks; ++r) finish_block<UPDATE>(a, qbase + (uint64_t)r * kThreads, outer[r]);
+}
+
+// Reconstruction for short vectors (too few Philox blocks to fill the chip with one thread per
+// block).  A workgroup owns 64 consecutive Philox blocks and has JS = blockDim.x / 64 waves; wave w
+// sums the vectors j = w, w + JS, w + 2 JS, ... for those blocks, the JS partial sums are added in
+// wave order through LDS, and wave 0 finishes the block.  Every wave regenerates only its own share
+// of the normals, so nothing is generated twice; the order of every sum is fixed by (d, m).
+constexpr int kSplitMaxWaves = 16;
+
+template <bool UPDATE>
+__global__ void __launch_bounds__(64 * kSplitMaxWaves) reconstruct_split_kernel(ReconArgs a)
+{
+    __shared__ float pb[kPbarTile];
+    extern __shared__ float red[];   // [JS][4][64], sized by the launch
+    const uint32_t t = threadIdx.x;
+    const uint32_t lane = t & 63u, w = t >> 6, JS = blockDim.x >> 6;
+    const uint64_t q64 = (uint64_t)blockIdx.x * 64 + lane;
+    const uint32_t q = (uint32_t)q64;
+
+    Generator<2, 3> gen;
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
+
+    float outer[4] = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t j0 = 0; j0 < a.m; j0 += kPbarTile) {
+        const uint32_t jn = (a.m - j0 < (uint32_t)kPbarTile) ? (a.m - j0) : (uint32_t)kPbarTile;
+        __syncthreads();
+        for (uint32_t x = t; x < jn; x += blockDim.x) pb[x] = a.pbar[j0 + x];
+        __syncthreads();
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};   // at most kPbarTile / JS <= 512 terms
+        for (uint32_t jj = w; jj < jn; jj += JS) {
+            const float p = pb[jj];
+            const Words wd = gen.words(q, j0 + jj);
+            float ra, ca, sa, rb, cb, sb;
+            gen.polar(wd.x0, wd.x1, ra, ca, sa);
+            gen.polar(wd.x2, wd.x3, rb, cb, sb);
+            const float pa = p * ra, pb2 = p * rb;
+            acc[0] = fmaf(pa, ca, acc[0]);
+            acc[1] = fmaf(pa, sa, acc[1]);
+            acc[2] = fmaf(pb2, cb, acc[2]);
+            acc[3] = fmaf(pb2, sb, acc[3]);
         }
-        if constexpr (UPDATE) {
-            float yv[4] = {0.f, 0.f, 0.f, 0.f}, xc[4] = {0.f, 0.f, 0.f, 0.f};
-            if (full) {
-                const float4 t4 = *reinterpret_cast<const float4*>(a.y + i);
-                yv[0] = t4.x; yv[1] = t4.y; yv[2] = t4.z; yv[3] = t4.w;
-                if (a.y_next) {
-                    const float4 c4 = *reinterpret_cast<const float4*>(a.x_cur + i);
-                    xc[0] = c4.x; xc[1] = c4.y; xc[2] = c4.z; xc[3] = c4.w;
-                }
-            } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) if (i + k < a.d) {
-                    yv[k] = a.y[i + k];
-                    if (a.y_next) xc[k] = a.x_cur[i + k];
-                }
-            }
-            const float h = a.h_dev ? *a.h_dev : a.h;
-            float xn[4], yn[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                xn[k] = fmaf(-h, v[k], yv[k]);
-                yn[k] = fmaf(a.omb, xn[k] - xc[k], xn[k]);
-            }
-            if (full) {
-                *reinterpret_cast<float4*>(a.x_new + i) = make_float4(xn[0], xn[1], xn[2], xn[3]);
-                if (a.y_next) *reinterpret_cast<float4*>(a.y_next + i) = make_float4(yn[0], yn[1], yn[2], yn[3]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) if (i + k < a.d) {
-                    a.x_new[i + k] = xn[k];
-                    if (a.y_next) a.y_next[i + k] = yn[k];
-                }
-            }
-        }
+        for (int k = 0; k < 4; ++k) outer[k] += acc[k];
     }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[(w * 4 + k) * 64 + lane] = outer[k];
+    __syncthreads();
+    if (w != 0) return;
+    float sum[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float s = red[k * 64 + lane];
+        for (uint32_t ww = 1; ww < JS; ++ww) s += red[(ww * 4 + k) * 64 + lane];
+        sum[k] = s;
+    }
+    finish_block<UPDATE>(a, q64, sum);
 }
 
 // Algorithm 3 (non-convex CORE-GD), Option I: the norm statistic p = c * sqrt(mean_j pbar_j^2)

@@ -155,16 +155,21 @@ def test_debug_exports_arguments():
     assert f(2, 1, 0, 0, 1 << 15, 0, 1 << 14, FAKE, None) == E.ERR_INVALID_ARGUMENT
     assert f(2, 1, 0, 0, 1, 0, 1, None, None) == E.ERR_INVALID_ARGUMENT
     assert f(2, 1, 0, 0, 1, 0, 1, FAKE + 2, None) == E.ERR_MISALIGNED
-    assert L.core_debug_set_projection(4) == E.ERR_INVALID_ARGUMENT
+    assert L.core_debug_set_projection(5) == E.ERR_INVALID_ARGUMENT
     assert L.core_debug_set_projection(-1) == E.ERR_INVALID_ARGUMENT
     # a forced kernel changes the plan (host arithmetic), and the default comes back
-    assert core.core_debug_plan(1024, 16, 4)["qmode"] == 1
-    core.core_debug_set_projection("valu")
+    assert core.core_debug_plan(1024, 16, 4)["mode"] == 2
     try:
-        assert core.core_debug_plan(1024, 16, 4)["qmode"] == 0
+        core.core_debug_set_projection("valu")
+        assert core.core_debug_plan(1024, 16, 4)["mode"] == 0
+        core.core_debug_set_projection("q")
+        assert core.core_debug_plan(1024, 16, 4)["mode"] == 1
+        core.core_debug_set_projection("small")
+        assert core.core_debug_plan(1024, 300, 4)["mode"] == 2
+        assert core.core_debug_plan(1024, 300, 9)["mode"] == 1
     finally:
         core.core_debug_set_projection("default")
-    assert core.core_debug_plan(1024, 16, 4)["qmode"] == 1
+    assert core.core_debug_plan(1024, 16, 4)["mode"] == 2
 
 
 def test_build_id_matches_the_sources():
@@ -354,7 +359,17 @@ def test_launch_plan_invariants():
     def check(d, m, n):
         p = core.core_debug_plan(d, m, n)
         assert p == core.core_debug_plan(d, m, n)
-        if p["qmode"]:
+        ws = core.core_workspace_bytes(d, m, n)
+        assert ws % 256 == 0
+        if p["mode"] == 2:
+            # one workgroup per vector over the whole of d: tiny problems only
+            assert n <= 8 and d <= 65536
+            assert (p["jtiles"], p["nchunks"], p["blocks"]) == (m, 1, m)
+            nblk = -(-d // 4)
+            threads = -(-nblk // p["tiles_per_chunk"])
+            assert p["tiles_per_chunk"] <= 16 and threads <= 1024   # fp32 chain of a thread: <= 64 terms
+            return
+        if p["mode"] == 1:
             tile, per_j = 1024, 4
             assert p["tiles_per_chunk"] <= 64
         else:
@@ -365,17 +380,20 @@ def test_launch_plan_invariants():
         assert (p["jtiles"] - 1) * per_j < m <= p["jtiles"] * per_j
         assert p["nchunks"] * p["jtiles"] <= p["blocks"] < (1 << 31)
         assert 1 <= p["slices"] <= 16
-        ws = core.core_workspace_bytes(d, m, n)
         assert ws >= 4 * p["nchunks"] * n * m + 8 * p["slices"] * n * m
-        assert ws % 256 == 0
 
     check()
     # the headline shapes keep the plan the profiles were taken with
     assert core.core_debug_plan(25_557_032, 1024, 8) == {
-        "qmode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160}
+        "mode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160}
     p5 = core.core_debug_plan(124_439_808, 4096, 16)
-    assert (p5["qmode"], p5["jtiles"], p5["tiles_per_chunk"]) == (0, 16, 950)
-    assert core.core_debug_plan(1024, 16, 4)["qmode"] == 1
+    assert (p5["mode"], p5["jtiles"], p5["tiles_per_chunk"]) == (0, 16, 950)
+    # the two launch-bound shapes take the one-launch plan, one Philox block per thread
+    assert core.core_debug_plan(1024, 16, 4) == {
+        "mode": 2, "jtiles": 16, "nchunks": 1, "tiles_per_chunk": 1, "slices": 1, "blocks": 16}
+    assert core.core_debug_plan(4096, 64, 8)["mode"] == 2
+    assert core.core_debug_plan(4096, 64, 9)["mode"] == 1          # more than 8 clients
+    assert core.core_debug_plan(1 << 20, 16, 4)["mode"] == 1       # few vectors, long gradient
     # sizes whose grid would not be launchable are refused up front
     import ctypes
     out = (ctypes.c_uint64 * 6)()

@@ -137,7 +137,7 @@ SHAPES = [
 ]
 
 
-@pytest.fixture(params=["default", "valu", "mfma", "q"])
+@pytest.fixture(params=["default", "valu", "mfma", "q", "small"])
 def variant(request):
     """Run a test once per projection kernel: the library's own choice, and each forced one."""
     core.core_debug_set_projection(request.param)
