@@ -31,6 +31,11 @@ constexpr uint32_t kMaxM = 0xFFFFFFFFu - 1023u;   // 2^32 - 1024
 constexpr uint32_t kMaxN = 65535u;
 constexpr uint32_t kMaxClientsPerPass = 16;       // VALU projection: accumulators held in registers per lane
 constexpr uint32_t kMaxClientsPerPassMfma = 32;   // matrix-pipe projection (8 groups of 4 clients)
+constexpr uint32_t kMaxClientsPerPassWide = 64;   // wide matrix-pipe projection (16 groups), one level of sums
+// The wide kernel adds every term of a chunk into one fp32 sum per (vector, client): chunks are kept
+// to 16 tiles = 4096 coordinates for calls that use it (rounding error of such a chain ~1e-6 of the
+// chunk's norm; the two-level kernels allow 1024 tiles).
+constexpr uint32_t kTilesPerChunkWide = 16;
 constexpr uint32_t kTargetBlocks = 8192;      // projection blocks wanted: 4 per resident slot
 
 inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -53,6 +58,7 @@ struct Plan {
     uint32_t tiles_per_chunk;
     uint32_t Z;            // slices of the cross-chunk sum
     uint32_t small_threads;   // kPlanSmall: threads per workgroup
+    bool wide;             // kPlanVectors with more than 32 clients: passes of up to 64 on the matrix pipe
     size_t part_off, psum_off, total;
 };
 
@@ -108,6 +114,7 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
     else if (forced == kVariantValu || forced == kVariantMfma) p.mode = kPlanVectors;
     else p.mode = !(allow_qmode && little_work) ? kPlanVectors : (small_ok ? kPlanSmall : kPlanCoords);
     p.small_threads = 0;
+    p.wide = false;
     if (p.mode == kPlanSmall) {
         // one Philox block per thread where d allows it: the serial chain of a thread is what a
         // launch-bound round waits for
@@ -137,6 +144,20 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
         if (const char* e = getenv("CORE_TPC")) tpc = strtoull(e, nullptr, 10);
 #endif
         if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
+        // more than 32 clients: wide passes, if the shorter chunks they need still give a launchable grid
+#ifdef CORE_EXPERIMENT
+        const bool no_wide = getenv("CORE_NOWIDE") != nullptr;
+#else
+        const bool no_wide = false;
+#endif
+        if (n > kMaxClientsPerPassMfma && forced != kVariantValu && !no_wide) {
+            const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
+            const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
+            if (ceil_div(chunks_wide, 8) * 8 * p.jtiles <= kMaxGridBlocks) {
+                p.wide = true;
+                tpc = tpc_wide;
+            }
+        }
         p.tiles_per_chunk = (uint32_t)tpc;
         p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
     }
@@ -223,6 +244,14 @@ hipError_t launch_project_mfma(const ProjectArgs& a, bool bf16, uint32_t blocks,
     const dim3 g(blocks), b(kThreads);
     return bf16 ? launch(project_mfma_kernel<NG, true>, g, b, st, a)
                 : launch(project_mfma_kernel<NG, false>, g, b, st, a);
+}
+
+template <int NG>
+hipError_t launch_project_mfma_wide(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+{
+    const dim3 g(blocks), b(kThreads);
+    return bf16 ? launch(project_mfma_wide_kernel<NG, true>, g, b, st, a)
+                : launch(project_mfma_wide_kernel<NG, false>, g, b, st, a);
 }
 
 template <int NC>
@@ -318,14 +347,29 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         const uint32_t left = n - c0;
         const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
         // Every pass regenerates the normals, so a pass takes as many clients as its kernel can
-        // hold: 32 on the matrix pipe (measured at 2^23 x 1024, bf16: n = 32 12.5 -> 8.9 ms,
-        // n = 50 22.1 -> 15.9 ms against passes of 16), 16 on the VALU.
+        // hold: 64 on the wide matrix-pipe kernel when more than 32 are left (ResNet-50-sized
+        // gradient, m = 1024, projection alone: n = 50 in one pass 32.6 ms against 48.2 ms in passes
+        // of 32 + 18, n = 64 39.5 against 52.9 ms, n = 36 25.4 against 37.4 ms), 32 on the two-level
+        // matrix-pipe kernel, 16 on the VALU.
         const bool mfma = !store && use_mfma_projection(left);
-        const uint32_t cap = mfma ? kMaxClientsPerPassMfma : kMaxClientsPerPass;
+        const bool wide = mfma && plan.wide && left > kMaxClientsPerPassMfma;
+        const uint32_t cap = wide ? kMaxClientsPerPassWide : mfma ? kMaxClientsPerPassMfma : kMaxClientsPerPass;
         const uint32_t nc = left < cap ? left : cap;
         a.c0 = c0; a.nc = nc;
         c0 += nc;
         hipError_t e;
+        if (wide) {
+            switch ((nc + 3) / 4) {   // client groups of 4: 9 to 16
+                case 9:  e = launch_project_mfma_wide<9>(a, bf16, blocks, st); break;
+                case 10: e = launch_project_mfma_wide<10>(a, bf16, blocks, st); break;
+                case 11: e = launch_project_mfma_wide<11>(a, bf16, blocks, st); break;
+                case 12: e = launch_project_mfma_wide<12>(a, bf16, blocks, st); break;
+                case 13: e = launch_project_mfma_wide<13>(a, bf16, blocks, st); break;
+                case 14: e = launch_project_mfma_wide<14>(a, bf16, blocks, st); break;
+                case 15: e = launch_project_mfma_wide<15>(a, bf16, blocks, st); break;
+                default: e = launch_project_mfma_wide<16>(a, bf16, blocks, st); break;
+            }
+        } else
         if (mfma) {
             if (nc <= 4)       e = launch_project_mfma<1>(a, bf16, blocks, st);
             else if (nc <= 8)  e = launch_project_mfma<2>(a, bf16, blocks, st);

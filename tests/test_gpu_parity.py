@@ -133,7 +133,8 @@ SHAPES = [
     (1, 1, 1), (2, 3, 2), (3, 1, 3), (4, 2, 1), (5, 2, 1), (7, 5, 4), (8, 4, 2),
     (255, 16, 5), (256, 63, 8), (257, 64, 9), (1023, 65, 16), (1025, 255, 17),
     (4099, 257, 3), (5000, 300, 20), (20000, 1, 7), (70001, 513, 2), (12345, 1030, 33),
-    (3000, 130, 32), (2500, 70, 29), (2000, 65, 50), (1500, 64, 64),   # passes of up to 32 clients
+    (3000, 130, 32), (2500, 70, 29), (2000, 65, 50), (1500, 64, 64),   # wide passes: up to 64 clients
+    (1500, 70, 44), (1300, 66, 47), (1100, 64, 55), (1000, 129, 58), (900, 65, 130),
 ]
 
 
@@ -231,6 +232,19 @@ def test_client_mean_commutes_with_the_round():
     p1 = core.core_compress(4, 4, gm, m)
     _sync()
     assert parity.rel_l2(p1.cpu().numpy(), pbar.cpu().numpy()) < 5e-6
+
+
+def test_many_clients_take_one_wide_pass_by_default():
+    """More than 32 clients on a shape large enough for the lanes-over-vectors plan: the library's
+    own choice is one generation of the normals for all 50 machines (Eq. (tildefdef): the same xi_j
+    serve every machine), on chunks short enough for one level of fp32 sums."""
+    d, m, n = 20000, 900, 50
+    plan = core.core_debug_plan(d, m, n)
+    assert plan["mode"] == 0 and plan["tiles_per_chunk"] <= 16
+    _say(f"wide pass by default d={d} m={m} n={n}")
+    rng = np.random.default_rng(50)
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
+    _run_and_check(9, 3, G, m, what=f"wide d={d} m={m} n={n}")
 
 
 def test_config3_full():
