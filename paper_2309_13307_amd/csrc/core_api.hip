@@ -262,9 +262,9 @@ hipError_t launch_project_q(const ProjectArgs& a, bool bf16, uint32_t blocks, hi
                 : launch(project_q_kernel<NC, false>, g, b, st, a);
 }
 
-// Which projection kernel serves a pass of nc clients.  Measured on MI355X (GPT-2-sized
-// gradient, n = 16): the matrix-pipe kernel is ~4 % faster than the VALU kernel at 16 clients and
-// ~5 % slower at 8, so it is the default above 8 clients.
+// Which projection kernel serves a pass of nc clients.  Measured on MI355X (ResNet-50-sized
+// gradient, m = 1024, every n from 9 to 16): the matrix-pipe kernel is 18-22 % faster than the VALU
+// kernel (which pads 9..15 clients to 16), and 1 % slower at 8, so it is the default above 8 clients.
 bool use_mfma_projection(uint32_t nc)
 {
     const int forced = forced_variant();
