@@ -72,10 +72,6 @@ constexpr uint32_t kQTilesPerChunkMax = 64;   // bounds the fp32 chains of the l
 constexpr uint32_t kTilesPerChunkMax = 1024;
 constexpr uint64_t kMaxGridBlocks = 0x7fffffffull;   // HIP's limit on gridDim.x
 
-// Split d into chunks of whole tiles so that (chunks x vector tiles) is about 8192 equal blocks:
-// four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens out speed differences
-// between CUs.  With fewer than 64 vectors, or too little work to fill the chip that way, the
-// lanes-over-q projection is planned instead.  Sizes depend only on (d, m, n).
 // Which projection kernel to use: the library's own choice, or one forced for A/B runs and for
 // the tests that drive every kernel over every shape.  Set with core_debug_set_projection (a
 // test-only export); the environment variable CORE_PROJECT_VARIANT=valu|mfma|q gives the initial
@@ -101,11 +97,15 @@ std::atomic<int>& variant_cell()
 
 inline int forced_variant() { return variant_cell().load(std::memory_order_relaxed); }
 
-bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
+// Split d into chunks of whole tiles so that (chunks x vector tiles) is about 8192 equal blocks:
+// four per resident block slot (256 CUs x 8 blocks of 4 waves), which evens out speed differences
+// between CUs.  With fewer than 64 vectors, or too little work to fill the chip that way, a
+// lanes-over-coordinates plan is made instead (in one launch, sums included, when the problem is tiny).
+// The plan depends only on (d, m, n) and on the forced kernel, if any.
+bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced, Plan& p)
 {
     if (d == 0 || d > kMaxD || m == 0 || m > kMaxM || n == 0 || n > kMaxN) return false;
     const uint64_t tiles_total = ceil_div(d, kTile);
-    const int forced = forced_variant();
     const bool small_ok = allow_qmode && n <= kSmallMaxClients && d <= kSmallMaxD && m <= 0x7fffffffu;
     const bool little_work = m < 64 || ceil_div(m, 64) * tiles_total <= 1024;
     const int coords_or_vectors = allow_qmode ? kPlanCoords : kPlanVectors;
@@ -179,12 +179,28 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
     return true;
 }
 
-// Workspace that serves every entry point for these sizes (either projection plan).
+bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, Plan& p)
+{
+    return make_plan(d, m, n, allow_qmode, forced_variant(), p);
+}
+
+// Workspace that serves every entry point for these sizes whichever projection kernel is chosen
+// or forced: a buffer sized once stays valid when the kernel choice is switched afterwards.
+// 0 if the sizes are out of range.
 size_t workspace_bytes(uint64_t d, uint32_t m, uint32_t n)
 {
-    Plan a, b;
-    if (!make_plan(d, m, n, true, a) || !make_plan(d, m, n, false, b)) return 0;
-    return a.total > b.total ? a.total : b.total;
+    const int current = forced_variant();
+    size_t need = 0;
+    for (int forced = kVariantAuto; forced <= kVariantSmall; ++forced)
+        for (int allow = 0; allow < 2; ++allow) {
+            Plan p;
+            if (!make_plan(d, m, n, allow != 0, forced, p)) {
+                if (forced == current) return 0;   // the plan a call would use now must exist
+                continue;                          // a forced kernel may not cover extreme sizes
+            }
+            if (p.total > need) need = p.total;
+        }
+    return need;
 }
 
 int hip_fail(hipError_t e)

@@ -159,7 +159,13 @@ def test_debug_exports_arguments():
     assert L.core_debug_set_projection(-1) == E.ERR_INVALID_ARGUMENT
     # a forced kernel changes the plan (host arithmetic), and the default comes back
     assert core.core_debug_plan(1024, 16, 4)["mode"] == 2
+    sizes = [(1024, 16, 4), (4096, 64, 8), (1 << 20, 256, 8), (25_557_032, 1024, 8), (70001, 513, 40)]
+    ws_default = [core.core_workspace_bytes(*sz) for sz in sizes]
     try:
+        for forced in ("valu", "mfma", "q", "small"):
+            # a workspace sized under one kernel choice serves every other one
+            core.core_debug_set_projection(forced)
+            assert [core.core_workspace_bytes(*sz) for sz in sizes] == ws_default
         core.core_debug_set_projection("valu")
         assert core.core_debug_plan(1024, 16, 4)["mode"] == 0
         core.core_debug_set_projection("q")

@@ -247,6 +247,33 @@ def test_many_clients_take_one_wide_pass_by_default():
     _run_and_check(9, 3, G, m, what=f"wide d={d} m={m} n={n}")
 
 
+def test_estimator_moments_on_the_device():
+    """Lemma 3.1 and the exact second moment from the proof of Lemma 3.2, checked on the HIP path
+    itself over many rounds of fresh vectors (independent of the element-wise comparison with the
+    oracle): E gtilde = gbar and E|gtilde - gbar|^2 = (d + 1)|gbar|^2 / m."""
+    d, m, n, S = 24, 6, 3, 6000
+    _say(f"estimator moments d={d} m={m} n={n} over {S} rounds")
+    rng = np.random.default_rng(31)
+    G_host = rng.standard_normal((n, d)).astype(np.float32)
+    G = torch.from_numpy(G_host).to(DEV)
+    gbar = G_host.astype(np.float64).mean(axis=0)
+    ws = core.alloc_workspace(d, m, n)
+    pbar = torch.empty(m, device=DEV)
+    out = torch.empty((S, d), device=DEV)
+    for r in range(S):
+        core.core_round(5, r, G, m, pbar=pbar, gtilde=out[r], ws=ws)
+    _sync()
+    gt = out.double().cpu().numpy()
+    # first moment: per-coordinate variance (|gbar|^2 + gbar_i^2)/m
+    var_i = (gbar @ gbar + gbar ** 2) / m
+    dev = np.abs(gt.mean(axis=0) - gbar) / np.sqrt(var_i / S)
+    assert dev.max() < 4.5, dev.max()
+    # second moment, with a confidence interval from the sample itself (heavy-tailed summand)
+    sq = ((gt - gbar) ** 2).sum(axis=1)
+    expect = (d + 1) * (gbar @ gbar) / m
+    assert abs(sq.mean() - expect) < 4.5 * sq.std(ddof=1) / np.sqrt(S), (sq.mean(), expect)
+
+
 def test_config3_full():
     case = workloads.config3(DEV)
     _say("config3 d=2^20 m=256 n=8 fp32 (oracle takes ~20 s)")
