@@ -90,6 +90,33 @@ def test_config4_full_size_sampled():
     assert 0.8 < ratio < 1.25, ratio
 
 
+@pytest.mark.timeout(400)
+def test_resnet50_size_with_50_clients_sampled():
+    """The paper's linear-model experiments use 50 machines: the ResNet-50-sized gradient with n = 50,
+    which takes the one-pass matrix-pipe projection (one generation of the normals for all 50
+    clients, one level of fp32 sums over chunks of 4096 coordinates).  Sampled vectors over the full d
+    and sampled coordinate blocks over all m, as for the other full-size cases."""
+    case = workloads.config4(DEV, n=50)
+    plan = core.core_debug_plan(case.d, case.m, case.n)
+    assert plan["mode"] == 0 and plan["tiles_per_chunk"] == 16
+    _say(f"config4 shape with n={case.n}: d={case.d} m={case.m} bf16, plan {plan}")
+    ws = core.alloc_workspace(case.d, case.m, case.n)
+    P, pbar = core.core_compress_batched(case.seed, 2, case.G, case.m, ws=ws)
+    pbar2, gtilde = core.core_round(case.seed, 2, case.G, case.m, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(pbar, pbar2)
+    assert bool(torch.isfinite(gtilde).all())
+    jidx = np.array([0, 3, 255, 256, 500, 767, 768, 1023], dtype=np.uint32)
+    G_host = workloads.to_host(case.G)
+    _sampled_check(case, 2, pbar, gtilde, jidx, 1024, "config4 n=50", G_host=G_host)
+    # the per-client projections too, for the sampled vectors
+    P_ref = _oracle_columns(case.seed, 2, G_host, jidx)
+    norms = np.array([float(torch.linalg.vector_norm(case.G[c].double())) for c in range(case.n)])
+    parity.check_projections(P.cpu().numpy()[:, jidx], P_ref, norms, case.d, case.m, "config4 n=50 P")
+    del case, G_host
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.timeout(900)
 def test_config5_full_size_sampled():
     case = workloads.config5(DEV)
