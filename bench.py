@@ -48,11 +48,16 @@ OPS_GENERATE = 26
 # compiled kernels at those shapes: they are reported only while the kernel sources still hash to
 # `kernel_id`, and as null otherwise.
 COUNTERS = {
-    "kernel_id": "unset",
+    "kernel_id": "f744563a0a30df2a",
     "config4": {
-        "source": "profiles/core_round_config4.md", "date": "unset",
-        "project": {"SQ_INSTS_VALU": 9.132e9, "fetch_bytes": 410.9e6, "write_bytes": 66.8e6},
-        "reconstruct": {"SQ_INSTS_VALU": 6.107e9, "fetch_bytes": 0.1e6, "write_bytes": 102.2e6},
+        "source": "profiles/core_round_config4.md", "date": "2026-11-27",
+        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200630 * 2 * 1024, "write_bytes": 65216 * 1024},
+        "reconstruct": {"SQ_INSTS_VALU": 6.10726e9, "fetch_bytes": 42 * 2 * 1024, "write_bytes": 99832.2 * 1024},
+    },
+    "config5": {
+        "source": "profiles/core_round_config5.md", "date": "2026-11-27",
+        "project": {"SQ_INSTS_VALU": 1.48462e11, "fetch_bytes": 1.94442e6 * 2 * 1024, "write_bytes": 131072 * 1024},
+        "reconstruct": {"SQ_INSTS_VALU": 1.18894e11, "fetch_bytes": 90 * 2 * 1024, "write_bytes": 486093 * 1024},
     },
 }
 

@@ -185,6 +185,15 @@ def test_build_id_matches_the_sources():
     assert not hip_build.is_stale()
 
 
+def test_bench_counter_constants_belong_to_the_current_kernels():
+    """bench.py reports counter-derived fields (issued instructions, HBM traffic) from constants read
+    with rocprofv3 beforehand, and only while the kernel sources hash to the value they were read
+    for.  A change to the kernels must come with a new profiler run (profiles/) and new constants."""
+    import bench
+    assert bench.COUNTERS["kernel_id"] == bench.kernel_id(), \
+        "kernel sources changed: re-collect the rocprofv3 counters and update bench.COUNTERS"
+
+
 def test_stale_library_is_detected(tmp_path):
     """A binary whose id differs from the hash of the sources counts as stale whatever its file time."""
     from paper_2309_13307_amd import build as hip_build
