@@ -85,6 +85,9 @@ def parse_args():
     ap.add_argument("--clients", type=int, default=None,
                     help="override the number of clients n of config4 / config5 (same recipe, more or fewer "
                          "rows of G); the workload name in the output says so")
+    ap.add_argument("--vectors", type=int, default=None,
+                    help="override the number of common vectors m of config4 / config5; the workload name "
+                         "in the output says so")
     ap.add_argument("--graph", action="store_true",
                     help="time the K rounds as one replay of a HIP graph that holds them (distinct round "
                          "counters by value): removes the host's launch cost, which is what the two "
@@ -301,6 +304,12 @@ def main():
         case.name += f" with n overridden to {args.clients}"
     else:
         case = make(dev)
+    if args.vectors is not None:
+        if args.workload not in ("config4", "config5") or args.vectors < 1:
+            print("bench.py: --vectors applies to config4 and config5 and must be >= 1", file=sys.stderr)
+            return 2
+        case.m = args.vectors
+        case.name += f" with m overridden to {args.vectors}"
     d, m, n = case.d, case.m, case.n
     mat = args.variant == "materialized"
 
@@ -318,7 +327,8 @@ def main():
 
     # counter-derived figures, only for the workloads they were collected on and only while the
     # kernels are the ones they were collected from
-    ctr = COUNTERS.get(args.workload) if (not mat and args.clients is None and not args.graph) else None
+    ctr = COUNTERS.get(args.workload) if (not mat and args.clients is None and args.vectors is None
+                                          and not args.graph) else None
     if ctr is not None and COUNTERS["kernel_id"] != kernel_id():
         ctr = None
 
@@ -393,7 +403,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case)
-    if not args.no_other_workloads and args.workload == "config4" and not mat and args.clients is None:
+    if (not args.no_other_workloads and args.workload == "config4" and not mat and args.clients is None
+            and args.vectors is None):
         del case
         torch.cuda.empty_cache()
         others = {}

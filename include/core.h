@@ -316,18 +316,21 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
 /* ---- test-only exports: raw generator output -------------------------------- */
 
 /* The launch plan core_compress_batched / core_round would use for these sizes (host arithmetic,
- * nothing is launched; `plan` is a HOST pointer):
- *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (few vectors or
- *           little work), 2 = one workgroup per vector with the sums finished inside it (tiny
+ * nothing is launched; `plan` is a HOST pointer to 8 values):
+ *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (at most 160
+ *           vectors, or little work), 2 = one workgroup per vector with the sums finished inside it (tiny
  *           problems with at most 8 clients and d <= 65536: projection, cross-chunk sum and client
  *           mean are then a single launch and the workspace is not used)
- *   plan[1] vector tiles (256 vectors each; groups of 4 vectors in mode 1; m in mode 2)
+ *   plan[1] vector tiles (256 vectors each; groups of plan[7] vectors in mode 1; m in mode 2)
  *   plan[2] chunks of d            plan[3] tiles per chunk (256 coordinates each; 1024 in mode 1;
  *                                          Philox blocks per thread in mode 2)
  *   plan[4] slices of the cross-chunk sum
- *   plan[5] projection blocks launched per pass of clients
+ *   plan[5] projection blocks launched per pass of clients (mode 0: by the lanes-over-vectors kernel)
+ *   plan[6] mode 0 only: how many of the last vectors (m mod 256, when at most 160) are projected by
+ *           a second, lanes-over-coordinates launch instead of a mostly idle block of 256; else 0
+ *   plan[7] vectors per block of the lanes-over-coordinates kernel (4 or 8; 0 if it is not used)
  * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */
-int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6]);
+int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[8]);
 
 /* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks <= 2^28.  out device uint32.
  * (Layout 0 of core_debug_philox_layout with one vector.) */

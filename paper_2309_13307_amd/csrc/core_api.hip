@@ -47,20 +47,33 @@ constexpr uint64_t kWaveSlots = 8192;    // resident waves at 8 per SIMD: 256 CU
 // How the projection is laid out on the chip.
 enum PlanMode : int {
     kPlanVectors = 0,   // lanes over the vectors j, blocks of 256 vectors x a chunk of 256-coordinate tiles
-    kPlanCoords = 1,    // lanes over the coordinates, blocks of kQJ vectors x a chunk of 1024-coordinate tiles
+    kPlanCoords = 1,    // lanes over the coordinates, blocks of 4 or 8 vectors x a chunk of 1024-coordinate tiles
     kPlanSmall = 2      // one workgroup per vector over the whole of d, sums finished inside it (one launch)
 };
 
 struct Plan {
     int mode;
-    uint32_t jtiles;       // vector tiles (256 vectors); groups of kQJ vectors (kPlanCoords); m (kPlanSmall)
+    uint32_t jtiles;       // tiles of 256 vectors given to the lanes-over-vectors kernels (0 in kPlanCoords;
+                           // m in kPlanSmall)
+    uint32_t tail_begin;   // first vector given to the lanes-over-coordinates kernel (= m when it gets none)
+    uint32_t tail_groups;  // its groups of qj vectors: all vectors in kPlanCoords, the last m mod 256 in
+                           // kPlanVectors when they would leave a block mostly idle, else 0
+    uint32_t qj;           // vectors per block of that kernel (4 or 8)
     uint32_t nchunks;
-    uint32_t tiles_per_chunk;
+    uint32_t tiles_per_chunk;   // in 256-coordinate tiles; a multiple of 4 whenever tail_groups > 0, because
+                                // the lanes-over-coordinates kernel walks 1024-coordinate tiles
     uint32_t Z;            // slices of the cross-chunk sum
     uint32_t small_threads;   // kPlanSmall: threads per workgroup
-    bool wide;             // kPlanVectors with more than 32 clients: passes of up to 64 on the matrix pipe
+    bool wide;             // more than 32 clients: passes of up to 64 on the matrix pipe
     size_t part_off, psum_off, total;
 };
+
+// Vectors left over after the tiles of 256 go to the lanes-over-coordinates kernel when there are at
+// most this many (measured on a ResNet-50-sized gradient, 8 clients, projection alone: 64 vectors
+// 1.04 ms against 1.71 ms in a quarter-filled lanes-over-vectors block, 128 vectors 2.04 against
+// 2.15 ms, 192 vectors 3.00 against 2.76 ms; 320 vectors as 256 + 64 instead of two tiles of which
+// one is a quarter full: 6.34 ms before).
+constexpr uint32_t kTailMax = 160;
 
 constexpr uint64_t kSmallMaxD = 65536;      // kPlanSmall: a thread's fp32 chain stays <= 256 terms
 constexpr uint32_t kSmallMaxClients = 8;
@@ -108,61 +121,90 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
     const uint64_t tiles_total = ceil_div(d, kTile);
     const bool small_ok = allow_qmode && n <= kSmallMaxClients && d <= kSmallMaxD && m <= 0x7fffffffu;
     const bool little_work = m < 64 || ceil_div(m, 64) * tiles_total <= 1024;
-    const int coords_or_vectors = allow_qmode ? kPlanCoords : kPlanVectors;
-    if (forced == kVariantQ) p.mode = coords_or_vectors;
-    else if (forced == kVariantSmall) p.mode = small_ok ? kPlanSmall : coords_or_vectors;
-    else if (forced == kVariantValu || forced == kVariantMfma) p.mode = kPlanVectors;
-    else p.mode = !(allow_qmode && little_work) ? kPlanVectors : (small_ok ? kPlanSmall : kPlanCoords);
+    const bool force_vectors = forced == kVariantValu || forced == kVariantMfma || !allow_qmode;
+    const uint32_t full_tiles = m / kThreads, rem = m % kThreads;
     p.small_threads = 0;
+    p.qj = 0;
     p.wide = false;
-    if (p.mode == kPlanSmall) {
+    p.tail_begin = m;
+    p.tail_groups = 0;
+    if (!force_vectors && small_ok && (forced == kVariantSmall || (forced == kVariantAuto && little_work))) {
         // one Philox block per thread where d allows it: the serial chain of a thread is what a
         // launch-bound round waits for
+        p.mode = kPlanSmall;
         uint64_t threads = ceil_div(ceil_div(d, 4), 64) * 64;
         if (threads > 1024) threads = 1024;
         p.small_threads = (uint32_t)threads;
         p.jtiles = m;
         p.nchunks = 1;
         p.tiles_per_chunk = (uint32_t)ceil_div(ceil_div(d, 4), threads);
-    } else if (p.mode == kPlanCoords) {
-        const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
-        p.jtiles = (uint32_t)ceil_div(m, kQJ);
-        uint64_t want = ceil_div(kTargetBlocks / 2, p.jtiles);
-        if (want < 1) want = 1;
-        if (want > qtiles) want = qtiles;
-        uint64_t tpc = ceil_div(qtiles, want);
-        if (tpc > kQTilesPerChunkMax) tpc = kQTilesPerChunkMax;
-        p.tiles_per_chunk = (uint32_t)tpc;
-        p.nchunks = (uint32_t)ceil_div(qtiles, tpc);
     } else {
-        p.jtiles = (uint32_t)ceil_div(m, kThreads);
-        uint64_t want = ceil_div(kTargetBlocks, p.jtiles);
-        if (want < 1) want = 1;
-        if (want > tiles_total) want = tiles_total;
-        uint64_t tpc = ceil_div(tiles_total, want);
-#ifdef CORE_EXPERIMENT
-        if (const char* e = getenv("CORE_TPC")) tpc = strtoull(e, nullptr, 10);
-#endif
-        if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
-        // more than 32 clients: wide passes, if the shorter chunks they need still give a launchable grid
-#ifdef CORE_EXPERIMENT
-        const bool no_wide = getenv("CORE_NOWIDE") != nullptr;
-#else
-        const bool no_wide = false;
-#endif
-        if (n > kMaxClientsPerPassMfma && forced != kVariantValu && !no_wide) {
-            const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
-            const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
-            if (ceil_div(chunks_wide, 8) * 8 * p.jtiles <= kMaxGridBlocks) {
-                p.wide = true;
-                tpc = tpc_wide;
-            }
+        // which vectors go to which kernel
+        bool coords_all = false, tail = false;
+        if (!force_vectors) {
+            if (forced == kVariantQ || forced == kVariantSmall) coords_all = true;
+            else coords_all = little_work || (full_tiles == 0 && rem <= kTailMax);
+            tail = !coords_all && full_tiles > 0 && rem > 0 && rem <= kTailMax;
         }
-        p.tiles_per_chunk = (uint32_t)tpc;
-        p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
+        const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
+        const uint32_t qvectors = coords_all ? m : (tail ? rem : 0);
+        if (qvectors) {
+            // 8 vectors per block share every load of G when there is enough work to fill the chip
+            // with such blocks; 4 otherwise (more, shorter blocks)
+            p.qj = (qvectors >= 16 && ceil_div(qvectors, 8) * qtiles >= 2 * kBlockSlots) ? 8 : 4;
+#ifdef CORE_EXPERIMENT
+            if (const char* e = getenv("CORE_QJ")) p.qj = (uint32_t)strtoul(e, nullptr, 10) == 8 ? 8 : 4;
+#endif
+            p.tail_begin = m - qvectors;
+            p.tail_groups = (uint32_t)ceil_div(qvectors, p.qj);
+        }
+        if (coords_all) {
+            p.mode = kPlanCoords;
+            p.jtiles = 0;
+            uint64_t want = ceil_div(kTargetBlocks / 2, p.tail_groups);
+            if (want < 1) want = 1;
+            if (want > qtiles) want = qtiles;
+            uint64_t tpcq = ceil_div(qtiles, want);
+            if (tpcq > kQTilesPerChunkMax) tpcq = kQTilesPerChunkMax;
+            p.tiles_per_chunk = (uint32_t)(4 * tpcq);
+            p.nchunks = (uint32_t)ceil_div(qtiles, tpcq);
+        } else {
+            p.mode = kPlanVectors;
+            p.jtiles = tail ? full_tiles : (uint32_t)ceil_div(m, kThreads);
+            uint64_t want = ceil_div(kTargetBlocks, p.jtiles);
+            if (want < 1) want = 1;
+            if (want > tiles_total) want = tiles_total;
+            uint64_t tpc = ceil_div(tiles_total, want);
+#ifdef CORE_EXPERIMENT
+            if (const char* e = getenv("CORE_TPC")) tpc = strtoull(e, nullptr, 10);
+#endif
+            if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
+            // more than 32 clients: wide passes, if the shorter chunks they need still give a launchable grid
+#ifdef CORE_EXPERIMENT
+            const bool no_wide = getenv("CORE_NOWIDE") != nullptr;
+#else
+            const bool no_wide = false;
+#endif
+            if (n > kMaxClientsPerPassMfma && forced != kVariantValu && !no_wide) {
+                const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
+                const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
+                if (ceil_div(chunks_wide, 8) * 8 * p.jtiles <= kMaxGridBlocks) {
+                    p.wide = true;
+                    tpc = tpc_wide;
+                }
+            }
+            if (tail) {   // both kernels must cut d at the same places: whole 1024-coordinate tiles
+                tpc = ceil_div(tpc, 4) * 4;
+                if (tpc > 4 * kQTilesPerChunkMax) tpc = 4 * kQTilesPerChunkMax;
+            }
+            p.tiles_per_chunk = (uint32_t)tpc;
+            p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
+        }
     }
-    // one block per (chunk, vector tile): the grid must stay a valid launch
-    const uint64_t grid = p.mode != kPlanVectors ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
+    // one block per (chunk, vector tile or group): both grids must stay valid launches
+    const uint64_t chunk_slots = ceil_div(p.nchunks, 8) * 8;
+    const uint64_t grid = p.mode == kPlanSmall ? (uint64_t)p.jtiles
+                                               : chunk_slots * (p.jtiles > p.tail_groups ? p.jtiles : p.tail_groups);
     if (grid > kMaxGridBlocks) return false;
     uint32_t Z = p.nchunks / 128u;
     if (Z < 1) Z = 1;
@@ -271,11 +313,13 @@ hipError_t launch_project_mfma_wide(const ProjectArgs& a, bool bf16, uint32_t bl
 }
 
 template <int NC>
-hipError_t launch_project_q(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+hipError_t launch_project_q(const ProjectArgs& a, bool bf16, uint32_t qj, uint32_t blocks, hipStream_t st)
 {
     const dim3 g(blocks), b(kThreads);
-    return bf16 ? launch(project_q_kernel<NC, true>, g, b, st, a)
-                : launch(project_q_kernel<NC, false>, g, b, st, a);
+    if (qj == 8) return bf16 ? launch(project_q_kernel<NC, true, 8>, g, b, st, a)
+                             : launch(project_q_kernel<NC, false, 8>, g, b, st, a);
+    return bf16 ? launch(project_q_kernel<NC, true, 4>, g, b, st, a)
+                : launch(project_q_kernel<NC, false, 4>, g, b, st, a);
 }
 
 // Which projection kernel serves a pass of nc clients.  Measured on MI355X (ResNet-50-sized
@@ -326,15 +370,17 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
     a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
     a.round_dev = reinterpret_cast<const uint32_t*>(round_dev);   // little-endian: lo word first
     a.jtiles = plan.jtiles; a.nchunks = plan.nchunks; a.tiles_per_chunk = plan.tiles_per_chunk;
+    a.j_begin = 0;
     a.part = part;
     a.xi_store = xi_store;
     const bool bf16 = (dt == CORE_DTYPE_BF16);
+    a.vec_load = (aligned_to(G, bf16 ? 8 : 16) && ld % 4 == 0) ? 1 : 0;
 
     if (plan.mode == kPlanSmall) {
         ProjectSmallArgs sa;
         sa.G = G; sa.ld = ld; sa.d = d; sa.m = m; sa.n = n;
         sa.k0 = a.k0; sa.k1 = a.k1; sa.r0 = a.r0; sa.r1 = a.r1; sa.round_dev = a.round_dev;
-        sa.vec_load = (aligned_to(G, bf16 ? 8 : 16) && ld % 4 == 0) ? 1 : 0;
+        sa.vec_load = a.vec_load;
         sa.P = P; sa.pbar = pbar;
         const dim3 g(m), b(plan.small_threads);
         hipError_t e;
@@ -345,20 +391,9 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         return e == hipSuccess ? CORE_OK : hip_fail(e);
     }
 
-    if (plan.mode == kPlanCoords) {
-        const uint32_t blocks = plan.nchunks * plan.jtiles;
-        for (uint32_t c0 = 0; c0 < n; c0 += 8) {
-            const uint32_t nc = (n - c0 < 8u) ? (n - c0) : 8u;
-            a.c0 = c0; a.nc = nc;
-            hipError_t e;
-            if (nc <= 1)      e = launch_project_q<1>(a, bf16, blocks, st);
-            else if (nc <= 2) e = launch_project_q<2>(a, bf16, blocks, st);
-            else if (nc <= 4) e = launch_project_q<4>(a, bf16, blocks, st);
-            else              e = launch_project_q<8>(a, bf16, blocks, st);
-            if (e != hipSuccess) return hip_fail(e);
-        }
-    } else {
-    const uint32_t blocks = (uint32_t)(ceil_div(plan.nchunks, 8) * 8 * plan.jtiles);
+    const uint32_t chunk_slots = (uint32_t)(ceil_div(plan.nchunks, 8) * 8);
+    if (plan.jtiles > 0) {   // lanes-over-vectors kernels: the tiles of 256 vectors
+    const uint32_t blocks = chunk_slots * plan.jtiles;
     for (uint32_t c0 = 0; c0 < n;) {
         const uint32_t left = n - c0;
         const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
@@ -401,6 +436,23 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         else              e = launch_project<16>(a, bf16, store, blocks, st);
         if (e != hipSuccess) return hip_fail(e);
     }
+    }
+    if (plan.tail_groups > 0) {   // lanes-over-coordinates kernel: all vectors, or the last m mod 256
+        ProjectArgs q = a;
+        q.jtiles = plan.tail_groups;
+        q.j_begin = plan.tail_begin;
+        q.tiles_per_chunk = plan.tiles_per_chunk / 4;   // its tiles are 1024 coordinates
+        const uint32_t blocks = chunk_slots * plan.tail_groups;
+        for (uint32_t c0 = 0; c0 < n; c0 += 8) {
+            const uint32_t nc = (n - c0 < 8u) ? (n - c0) : 8u;
+            q.c0 = c0; q.nc = nc;
+            hipError_t e;
+            if (nc <= 1)      e = launch_project_q<1>(q, bf16, plan.qj, blocks, st);
+            else if (nc <= 2) e = launch_project_q<2>(q, bf16, plan.qj, blocks, st);
+            else if (nc <= 4) e = launch_project_q<4>(q, bf16, plan.qj, blocks, st);
+            else              e = launch_project_q<8>(q, bf16, plan.qj, blocks, st);
+            if (e != hipSuccess) return hip_fail(e);
+        }
     }
 
     const uint64_t E = (uint64_t)n * m;
@@ -907,16 +959,19 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
     return enqueue_reconstruct_xi(d, m, pbar, 1.0f / (float)m, xi, gtilde, (hipStream_t)stream);
 }
 
-int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[6])
+int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[8])
 {
     Plan p;
     if (!plan || !make_plan(d, m, n, true, p)) return CORE_ERR_INVALID_ARGUMENT;
+    const uint64_t chunk_slots = ceil_div(p.nchunks, 8) * 8;
     plan[0] = (uint64_t)p.mode;
-    plan[1] = p.jtiles;
+    plan[1] = p.mode == kPlanCoords ? p.tail_groups : p.jtiles;
     plan[2] = p.nchunks;
-    plan[3] = p.tiles_per_chunk;
+    plan[3] = p.mode == kPlanCoords ? p.tiles_per_chunk / 4 : p.tiles_per_chunk;
     plan[4] = p.Z;
-    plan[5] = p.mode != kPlanVectors ? (uint64_t)p.nchunks * p.jtiles : ceil_div(p.nchunks, 8) * 8 * p.jtiles;
+    plan[5] = p.mode == kPlanSmall ? (uint64_t)p.jtiles : chunk_slots * plan[1];
+    plan[6] = p.mode == kPlanVectors ? (uint64_t)(m - p.tail_begin) : 0;
+    plan[7] = p.qj;
     return CORE_OK;
 }
 

@@ -19,6 +19,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "core_rng.hpp"
 
@@ -39,11 +40,15 @@ struct ProjectArgs {
     uint32_t k0, k1;      // seed halves
     uint32_t r0, r1;      // round halves
     const uint32_t* round_dev;   // when non-null, the round counter (lo, hi) is read from here instead
-    uint32_t jtiles;      // ceil(m / kThreads)
+    uint32_t jtiles;      // vector tiles of this launch: tiles of kThreads vectors, or groups of QJ vectors
+    uint32_t j_begin;     // lanes-over-coordinates kernel: first vector of this launch (its groups cover
+                          // j_begin .. m-1; the vectors below belong to a lanes-over-vectors launch)
     uint32_t nchunks;     // chunks of d
     uint32_t tiles_per_chunk;
     float* part;          // [nchunks][n][m]
     float* xi_store;      // materialised variant only: [ceil(d/4)][m][4], else unused
+    int vec_load;         // lanes-over-coordinates kernel: rows of G start on 16-byte (fp32) / 8-byte (bf16)
+                          // boundaries, so a thread may fetch its 4 coordinates with one load
 };
 
 template <bool BF16>
@@ -364,22 +369,90 @@ project_mfma_wide_kernel(ProjectArgs a)
     }
 }
 
-// Projection for few vectors or little work (m < 64, or too few tiles to fill the chip with the
-// lanes-over-j kernels above).  Lanes run over the Philox block q, as in the reconstruction; a block
-// owns kQJ consecutive vectors and a chunk of 1024-coordinate tiles.  Each thread keeps G for its 4
-// coordinates in registers, generates the kQJ normals blocks, and accumulates its share of the kQJ x NC
-// sums; the sums are combined across the block once per chunk (wave butterfly, then LDS in wave order).
-// All lanes do useful work whatever m is, and a tiny problem is spread over many short blocks.
-constexpr int kQJ = 4;
+// Projection for few vectors, for the last m mod 256 vectors of a larger problem, or for little work.
+// With lanes over the vectors a block of 256 threads needs 256 vectors to keep its four waves busy (and
+// the busy waves of partly filled blocks pile up on the same SIMDs); here lanes run over the Philox
+// block q, as in the reconstruction, so every lane works whatever the number of vectors is.  A block owns QJ consecutive vectors and a
+// chunk of 1024-coordinate tiles; each thread loads G for its 4 coordinates once per tile (one 64- or
+// 128-bit load per client when the rows allow it) and keeps it in registers for all QJ vectors, so
+// there is no LDS traffic in the loop; the QJ x NC sums are combined across the block once per chunk
+// (wave butterfly, then LDS in wave order; fixed order).
+template <bool BF16>
+__device__ __forceinline__ void load_g4(const void* G, uint64_t base, uint64_t i, uint64_t d, bool vec, float (&g)[4])
+{
+    if (vec && i + 4 <= d) {
+        if constexpr (BF16) {
+            const uint2 v = *reinterpret_cast<const uint2*>((const uint16_t*)G + base);
+            g[0] = __uint_as_float(v.x << 16); g[1] = __uint_as_float(v.x & 0xffff0000u);
+            g[2] = __uint_as_float(v.y << 16); g[3] = __uint_as_float(v.y & 0xffff0000u);
+        } else {
+            const float4 v = *reinterpret_cast<const float4*>((const float*)G + base);
+            g[0] = v.x; g[1] = v.y; g[2] = v.z; g[3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) g[k] = (i + k < d) ? load_g<BF16>(G, base + k) : 0.0f;
+    }
+}
 
-template <int NC, bool BF16>
+// The 4 coordinates of one client as they come from memory, kept in that form while the loads are
+// in flight (prefetch of the next tile) and widened to fp32 only when the tile is used.
+template <bool BF16> struct RawG4;
+
+template <> struct RawG4<false> {
+    float v[4];
+    __device__ __forceinline__ void load(const void* G, uint64_t base, uint64_t i, uint64_t d, bool vec)
+    {
+        if (vec && i + 4 <= d) {
+            const float4 x = *reinterpret_cast<const float4*>((const float*)G + base);
+            v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = (i + k < d) ? ((const float*)G)[base + k] : 0.0f;
+        }
+    }
+    __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0.0f; }
+    __device__ __forceinline__ void widen(float (&g)[4]) const { g[0] = v[0]; g[1] = v[1]; g[2] = v[2]; g[3] = v[3]; }
+};
+
+template <> struct RawG4<true> {
+    uint32_t lo, hi;   // bf16 pairs: coordinates (0, 1) and (2, 3)
+    __device__ __forceinline__ void load(const void* G, uint64_t base, uint64_t i, uint64_t d, bool vec)
+    {
+        const uint16_t* p = (const uint16_t*)G + base;
+        if (vec && i + 4 <= d) {
+            const uint2 x = *reinterpret_cast<const uint2*>(p);
+            lo = x.x; hi = x.y;
+        } else {
+            uint32_t e[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) e[k] = (i + k < d) ? (uint32_t)p[k] : 0u;
+            lo = e[0] | (e[1] << 16); hi = e[2] | (e[3] << 16);
+        }
+    }
+    __device__ __forceinline__ void zero() { lo = hi = 0u; }
+    __device__ __forceinline__ void widen(float (&g)[4]) const
+    {
+        g[0] = __uint_as_float(lo << 16); g[1] = __uint_as_float(lo & 0xffff0000u);
+        g[2] = __uint_as_float(hi << 16); g[3] = __uint_as_float(hi & 0xffff0000u);
+    }
+};
+
+template <int NC, bool BF16, int QJ>
 __global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
 {
-    __shared__ float red[kThreads / 64][kQJ * NC];
+    __shared__ float red[kThreads / 64][QJ * NC];
     const uint32_t t = threadIdx.x;
-    const uint32_t jg = blockIdx.x % a.jtiles;          // a.jtiles = groups of kQJ vectors here
-    const uint32_t chunk = blockIdx.x / a.jtiles;
-    const uint32_t j0 = jg * kQJ;
+    // As in project_kernel: consecutive block ids go round-robin over the 8 XCDs, so all vector groups
+    // of one chunk of G are given ids congruent mod 8 and the chunk is fetched into a single L2
+    // (each group re-reads the chunk: m / QJ times in all).
+    const uint32_t b = blockIdx.x;
+    const uint32_t xcd = b & 7u;
+    const uint32_t s = b >> 3;
+    const uint32_t chunk = (s / a.jtiles) * 8u + xcd;   // a.jtiles = groups of QJ vectors here
+    const uint32_t jg = s % a.jtiles;
+    if (chunk >= a.nchunks) return;
+    const uint32_t j0 = a.j_begin + jg * QJ;
 
     const uint64_t qtile = (uint64_t)kThreads * 4;      // coordinates per tile
     const uint64_t tiles_total = (a.d + qtile - 1) / qtile;
@@ -390,42 +463,57 @@ __global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
     Generator<2, 3> gen;
     gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
 
-    float acc[kQJ][NC];
+    float acc[QJ][NC];
 #pragma unroll
-    for (int jj = 0; jj < kQJ; ++jj)
+    for (int jj = 0; jj < QJ; ++jj)
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[jj][c] = 0.0f;
 
-    for (uint64_t tl = tile_begin; tl < tile_end; ++tl) {
-        const uint64_t q = tl * kThreads + t;
-        const uint64_t i = 4 * q;
-        float g[NC][4];
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float v = 0.0f;
-                if (i + k < a.d && (uint32_t)c < a.nc) v = load_g<BF16>(a.G, (uint64_t)(a.c0 + c) * a.ld + i + k);
-                g[c][k] = v;
-            }
-#pragma unroll
-        for (int jj = 0; jj < kQJ; ++jj) {
-            if (j0 + jj >= a.m) break;                   // block-uniform
-            float z0, z1, z2, z3;
-            gen.block((uint32_t)q, j0 + jj, z0, z1, z2, z3);
+    // A group with all QJ vectors present (every group but possibly the last) runs a loop body
+    // without branches, so that the QJ independent generator calls can be interleaved.  The next
+    // tile of G is fetched into registers before the current one is used: the workgroups of a CU
+    // start together and stay in phase, so without it they would all wait for memory at once.
+    auto walk = [&](auto full_group) {
+        constexpr bool kFull = decltype(full_group)::value;
+        RawG4<BF16> raw[NC];
+        auto fetch = [&](uint64_t tl) {
+            const uint64_t i = 4 * (tl * kThreads + t);
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                acc[jj][c] = fmaf(z0, g[c][0], acc[jj][c]);
-                acc[jj][c] = fmaf(z1, g[c][1], acc[jj][c]);
-                acc[jj][c] = fmaf(z2, g[c][2], acc[jj][c]);
-                acc[jj][c] = fmaf(z3, g[c][3], acc[jj][c]);
+                if ((uint32_t)c < a.nc) raw[c].load(a.G, (uint64_t)(a.c0 + c) * a.ld + i, i, a.d, a.vec_load != 0);
+                else                    raw[c].zero();
+            }
+        };
+        if (tile_begin < tile_end) fetch(tile_begin);
+        for (uint64_t tl = tile_begin; tl < tile_end; ++tl) {
+            const uint64_t q = tl * kThreads + t;
+            float g[NC][4];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) raw[c].widen(g[c]);
+            if (tl + 1 < tile_end) fetch(tl + 1);
+#pragma unroll
+            for (int jj = 0; jj < QJ; ++jj) {
+                if constexpr (!kFull) {
+                    if (j0 + jj >= a.m) break;           // block-uniform
+                }
+                float z0, z1, z2, z3;
+                gen.block((uint32_t)q, j0 + jj, z0, z1, z2, z3);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    acc[jj][c] = fmaf(z0, g[c][0], acc[jj][c]);
+                    acc[jj][c] = fmaf(z1, g[c][1], acc[jj][c]);
+                    acc[jj][c] = fmaf(z2, g[c][2], acc[jj][c]);
+                    acc[jj][c] = fmaf(z3, g[c][3], acc[jj][c]);
+                }
             }
         }
-    }
+    };
+    if (j0 + QJ <= a.m) walk(std::true_type{});
+    else                walk(std::false_type{});
 
     // fixed-order combination: butterfly inside each wave, then waves 0..3 in order
 #pragma unroll
-    for (int jj = 0; jj < kQJ; ++jj)
+    for (int jj = 0; jj < QJ; ++jj)
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             float v = acc[jj][c];
@@ -434,7 +522,7 @@ __global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
             if ((t & 63u) == 0) red[t >> 6][jj * NC + c] = v;
         }
     __syncthreads();
-    if (t < (uint32_t)(kQJ * NC)) {
+    if (t < (uint32_t)(QJ * NC)) {
         const uint32_t jj = t / NC, c = t % NC;
         if (j0 + jj < a.m && c < a.nc) {
             float tot = red[0][t];
@@ -486,23 +574,10 @@ __global__ void __launch_bounds__(1024) project_small_kernel(ProjectSmallArgs a)
         float g[NC][4];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            g[c][0] = g[c][1] = g[c][2] = g[c][3] = 0.0f;
             if ((uint32_t)c < a.n) {
-                const uint64_t base = (uint64_t)c * a.ld + i;
-                if (a.vec_load && i + 4 <= a.d) {
-                    if constexpr (BF16) {
-                        const uint2 v = *reinterpret_cast<const uint2*>((const uint16_t*)a.G + base);
-                        g[c][0] = __uint_as_float(v.x << 16); g[c][1] = __uint_as_float(v.x & 0xffff0000u);
-                        g[c][2] = __uint_as_float(v.y << 16); g[c][3] = __uint_as_float(v.y & 0xffff0000u);
-                    } else {
-                        const float4 v = *reinterpret_cast<const float4*>((const float*)a.G + base);
-                        g[c][0] = v.x; g[c][1] = v.y; g[c][2] = v.z; g[c][3] = v.w;
-                    }
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        if (i + k < a.d) g[c][k] = load_g<BF16>(a.G, base + k);
-                }
+                load_g4<BF16>(a.G, (uint64_t)c * a.ld + i, i, a.d, a.vec_load != 0, g[c]);
+            } else {
+                g[c][0] = g[c][1] = g[c][2] = g[c][3] = 0.0f;
             }
         }
         float z0, z1, z2, z3;

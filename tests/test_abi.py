@@ -113,7 +113,7 @@ def test_vector_count_limit():
         assert L.core_reconstruct_update_batched(1, 0, 4, m, 1, FAKE, 1 << 32, 0.25, 0.1, FAKE + (1 << 40), None, 4,
                                                  None) == E.ERR_INVALID_ARGUMENT
         assert L.core_reconstruct_from_xi(4, m, FAKE, 0.1, FAKE + 64, 1 << 40, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
-        out = (ctypes.c_uint64 * 6)()
+        out = (ctypes.c_uint64 * 8)()
         assert L.core_debug_plan(4, m, 1, out) == E.ERR_INVALID_ARGUMENT
     # the largest accepted count passes validation (it then needs a device, or a workspace nobody has)
     assert core.core_workspace_bytes(4, top, 1) > 0
@@ -385,14 +385,22 @@ def test_launch_plan_invariants():
             assert p["tiles_per_chunk"] <= 16 and threads <= 1024   # fp32 chain of a thread: <= 64 terms
             return
         if p["mode"] == 1:
-            tile, per_j = 1024, 4
+            tile, per_j, covered = 1024, p["vectors_per_block"], m
+            assert per_j in (4, 8) and p["tail_vectors"] == 0
             assert p["tiles_per_chunk"] <= 64
         else:
             tile, per_j = 256, 256
             assert p["tiles_per_chunk"] <= 1024
+            # the last m mod 256 vectors may go to a second, lanes-over-coordinates launch
+            tail = p["tail_vectors"]
+            covered = m - tail
+            if tail:
+                assert 0 < tail == m % 256 <= 160 and p["vectors_per_block"] in (4, 8)
+                assert p["tiles_per_chunk"] % 4 == 0 and covered % 256 == 0 and covered > 0
+                assert -(-tail // p["vectors_per_block"]) * -(-p["nchunks"] // 8) * 8 < (1 << 31)
         tiles = -(-d // tile)
         assert (p["nchunks"] - 1) * p["tiles_per_chunk"] < tiles <= p["nchunks"] * p["tiles_per_chunk"]
-        assert (p["jtiles"] - 1) * per_j < m <= p["jtiles"] * per_j
+        assert (p["jtiles"] - 1) * per_j < covered <= p["jtiles"] * per_j
         assert p["nchunks"] * p["jtiles"] <= p["blocks"] < (1 << 31)
         assert 1 <= p["slices"] <= 16
         assert ws >= 4 * p["nchunks"] * n * m + 8 * p["slices"] * n * m
@@ -400,18 +408,29 @@ def test_launch_plan_invariants():
     check()
     # the headline shapes keep the plan the profiles were taken with
     assert core.core_debug_plan(25_557_032, 1024, 8) == {
-        "mode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160}
+        "mode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160,
+        "tail_vectors": 0, "vectors_per_block": 0}
     p5 = core.core_debug_plan(124_439_808, 4096, 16)
     assert (p5["mode"], p5["jtiles"], p5["tiles_per_chunk"]) == (0, 16, 950)
     # the two launch-bound shapes take the one-launch plan, one Philox block per thread
     assert core.core_debug_plan(1024, 16, 4) == {
-        "mode": 2, "jtiles": 16, "nchunks": 1, "tiles_per_chunk": 1, "slices": 1, "blocks": 16}
+        "mode": 2, "jtiles": 16, "nchunks": 1, "tiles_per_chunk": 1, "slices": 1, "blocks": 16,
+        "tail_vectors": 0, "vectors_per_block": 0}
     assert core.core_debug_plan(4096, 64, 8)["mode"] == 2
     assert core.core_debug_plan(4096, 64, 9)["mode"] == 1          # more than 8 clients
     assert core.core_debug_plan(1 << 20, 16, 4)["mode"] == 1       # few vectors, long gradient
+    # up to 160 vectors on a long gradient: lanes over coordinates, 8 vectors per block
+    p160 = core.core_debug_plan(25_557_032, 160, 8)
+    assert (p160["mode"], p160["jtiles"], p160["vectors_per_block"]) == (1, 20, 8)
+    assert core.core_debug_plan(25_557_032, 161, 8)["mode"] == 0
+    # ragged vector counts: whole tiles of 256 to the lanes-over-vectors kernel, a short rest to the other
+    p320 = core.core_debug_plan(25_557_032, 320, 8)
+    assert (p320["mode"], p320["jtiles"], p320["tail_vectors"], p320["tiles_per_chunk"] % 4) == (0, 1, 64, 0)
+    p1000 = core.core_debug_plan(25_557_032, 1000, 8)     # 3 x 256 + 232: the rest fills a block well enough
+    assert (p1000["jtiles"], p1000["tail_vectors"]) == (4, 0)
     # sizes whose grid would not be launchable are refused up front
     import ctypes
-    out = (ctypes.c_uint64 * 6)()
+    out = (ctypes.c_uint64 * 8)()
     L = core.load_library()
     assert L.core_debug_plan(1 << 34, (1 << 32) - 1, 1, out) == binding.ERR_INVALID_ARGUMENT
     assert core.core_workspace_bytes(1 << 34, (1 << 32) - 1, 1) == 0

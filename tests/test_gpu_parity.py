@@ -458,6 +458,30 @@ def test_streams_and_graph_capture():
         assert bool(torch.isfinite(tmp))
 
 
+@pytest.mark.parametrize("d,m,n,bf16", [
+    (60000, 320, 8, False),     # 256 vectors to the lanes-over-vectors kernel + 64 to the lanes-over-coordinates one
+    (40000, 600, 3, True),      # 512 + 88
+    (53000, 257, 16, True),     # 256 on the matrix pipe + 1, the rest in two passes of 8 clients
+    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 76
+    (300000, 130, 2, False),    # fewer than 161 vectors on a long gradient: lanes over coordinates throughout
+    (66000, 200, 4, False),     # 200 vectors: one partly filled block of 256
+    (70001, 513, 2, False),     # 512 + 1
+])
+def test_ragged_vector_counts_split_between_the_two_projections(d, m, n, bf16):
+    """Vector counts that are not multiples of 256, on shapes with enough work for the
+    lanes-over-vectors plan: the library's own choice gives the whole tiles to that kernel and a short
+    rest to the lanes-over-coordinates kernel, both writing the same per-chunk partial sums."""
+    plan = core.core_debug_plan(d, m, n)
+    _say(f"ragged vector count d={d} m={m} n={n} bf16={bf16} plan={plan}")
+    if m % 256 and m % 256 <= 160 and m > 256:
+        assert plan["mode"] == 0 and plan["tail_vectors"] == m % 256
+    rng = np.random.default_rng(d + 3 * m + n)
+    G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
+    if bf16:
+        G = G.to(torch.bfloat16)
+    _run_and_check(61, 2, G, m, what=f"ragged m d={d} m={m} n={n}")
+
+
 @pytest.mark.parametrize("d,m,n", [(300, 20000, 2), (2000, 5, 100), (20000, 2100, 1)])
 def test_extreme_aspect_ratios(d, m, n, variant):
     """Many vectors on a short gradient, many clients (several passes), one client on a long one."""
