@@ -151,7 +151,7 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
         if (qvectors) {
             // 8 vectors per block share every load of G when there is enough work to fill the chip
             // with such blocks; 4 otherwise (more, shorter blocks)
-            p.qj = (qvectors >= 16 && ceil_div(qvectors, 8) * qtiles >= 2 * kBlockSlots) ? 8 : 4;
+            p.qj = (qvectors > 4 && ceil_div(qvectors, 8) * qtiles >= 2 * kBlockSlots) ? 8 : 4;
 #ifdef CORE_EXPERIMENT
             if (const char* e = getenv("CORE_QJ")) p.qj = (uint32_t)strtoul(e, nullptr, 10) == 8 ? 8 : 4;
 #endif
