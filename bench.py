@@ -48,15 +48,15 @@ OPS_GENERATE = 26
 # compiled kernels at those shapes: they are reported only while the kernel sources still hash to
 # `kernel_id`, and as null otherwise.
 COUNTERS = {
-    "kernel_id": "f744563a0a30df2a",
+    "kernel_id": "16cf18c6d4b234c3",
     "config4": {
         "source": "profiles/core_round_config4.md", "date": "2026-11-27",
-        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200630 * 2 * 1024, "write_bytes": 65216 * 1024},
+        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200635 * 2 * 1024, "write_bytes": 65216 * 1024},
         "reconstruct": {"SQ_INSTS_VALU": 6.10726e9, "fetch_bytes": 42 * 2 * 1024, "write_bytes": 99832.2 * 1024},
     },
     "config5": {
         "source": "profiles/core_round_config5.md", "date": "2026-11-27",
-        "project": {"SQ_INSTS_VALU": 1.48462e11, "fetch_bytes": 1.94442e6 * 2 * 1024, "write_bytes": 131072 * 1024},
+        "project": {"SQ_INSTS_VALU": 1.48462e11, "fetch_bytes": 1.94443e6 * 2 * 1024, "write_bytes": 131072 * 1024},
         "reconstruct": {"SQ_INSTS_VALU": 1.18894e11, "fetch_bytes": 90 * 2 * 1024, "write_bytes": 486093 * 1024},
     },
 }
