@@ -316,8 +316,8 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
 /* ---- test-only exports: raw generator output -------------------------------- */
 
 /* The launch plan core_compress_batched / core_round would use for these sizes (host arithmetic,
- * nothing is launched; `plan` is a HOST pointer to 8 values):
- *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (at most 160
+ * nothing is launched; `plan` is a HOST pointer to 10 values):
+ *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (at most 48
  *           vectors, or little work), 2 = one workgroup per vector with the sums finished inside it (tiny
  *           problems with at most 8 clients and d <= 65536: projection, cross-chunk sum and client
  *           mean are then a single launch and the workspace is not used)
@@ -325,12 +325,14 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
  *   plan[2] chunks of d            plan[3] tiles per chunk (256 coordinates each; 1024 in mode 1;
  *                                          Philox blocks per thread in mode 2)
  *   plan[4] slices of the cross-chunk sum
- *   plan[5] projection blocks launched per pass of clients (mode 0: by the lanes-over-vectors kernel)
- *   plan[6] mode 0 only: how many of the last vectors (m mod 256, when at most 160) are projected by
- *           a second, lanes-over-coordinates launch instead of a mostly idle block of 256; else 0
+ *   plan[5] projection blocks launched per pass of clients (mode 0: by the 256-vector kernel)
+ *   Mode 0 serves the rest m mod 256, when it is at most 192, without half-empty blocks of 256:
+ *   plan[8] one-wave blocks of 64 vectors that follow the tiles of 256 (a second launch), and
+ *   plan[6] the last vectors (at most 48) projected by a lanes-over-coordinates launch instead;
  *   plan[7] vectors per block of the lanes-over-coordinates kernel (4 or 8; 0 if it is not used)
+ *   plan[9] reserved (0)
  * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */
-int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[8]);
+int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[10]);
 
 /* out[b][0..3] = Philox words of block q0 + b of vector j,  b < nblocks <= 2^28.  out device uint32.
  * (Layout 0 of core_debug_philox_layout with one vector.) */

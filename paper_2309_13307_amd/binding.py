@@ -426,10 +426,11 @@ def core_advance_round(round_dev: torch.Tensor) -> None:
 
 def core_debug_plan(d: int, m: int, n: int) -> dict:
     """The projection launch plan for these sizes (host arithmetic only)."""
-    out = (ctypes.c_uint64 * 8)()
+    out = (ctypes.c_uint64 * 10)()
     rc = load_library().core_debug_plan(d, m, n, out)
     _check(rc, "core_debug_plan")
-    keys = ("mode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks", "tail_vectors", "vectors_per_block")
+    keys = ("mode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks", "tail_vectors", "vectors_per_block",
+            "narrow_tiles")
     return dict(zip(keys, (int(v) for v in out)))
 
 

@@ -55,9 +55,11 @@ struct Plan {
     int mode;
     uint32_t jtiles;       // tiles of 256 vectors given to the lanes-over-vectors kernels (0 in kPlanCoords;
                            // m in kPlanSmall)
+    uint32_t narrow_tiles; // tiles of 64 vectors after those, given to project_narrow_kernel (whole waves of
+                           // vectors that would not fill a block of 256)
     uint32_t tail_begin;   // first vector given to the lanes-over-coordinates kernel (= m when it gets none)
-    uint32_t tail_groups;  // its groups of qj vectors: all vectors in kPlanCoords, the last m mod 256 in
-                           // kPlanVectors when they would leave a block mostly idle, else 0
+    uint32_t tail_groups;  // its groups of qj vectors: all vectors in kPlanCoords; in kPlanVectors the
+                           // last m mod 64 when they are too few for a wave of their own; else 0
     uint32_t qj;           // vectors per block of that kernel (4 or 8)
     uint32_t nchunks;
     uint32_t tiles_per_chunk;   // in 256-coordinate tiles; a multiple of 4 whenever tail_groups > 0, because
@@ -68,12 +70,19 @@ struct Plan {
     size_t part_off, psum_off, total;
 };
 
-// Vectors left over after the tiles of 256 go to the lanes-over-coordinates kernel when there are at
-// most this many (measured on a ResNet-50-sized gradient, 8 clients, projection alone: 64 vectors
-// 1.04 ms against 1.71 ms in a quarter-filled lanes-over-vectors block, 128 vectors 2.04 against
-// 2.15 ms, 192 vectors 3.00 against 2.76 ms; 320 vectors as 256 + 64 instead of two tiles of which
-// one is a quarter full: 6.34 ms before).
-constexpr uint32_t kTailMax = 160;
+// How the vectors that do not fill a tile of 256 are served (m mod 256 = rest).  A wave of the
+// lanes-over-vectors kernels is latency-bound on its own and only about 8 busy waves per SIMD saturate
+// the issue port, so a block of 256 with idle waves wastes wave slots: measured on a ResNet-50-sized
+// gradient (8 clients, projection alone), 64 vectors as a quarter-filled block 1.71 ms, 320 vectors as
+// one full and one quarter-filled tile 6.34 ms against 3.35 ms for 256.  So: a rest above 192 fills all
+// four waves of one more block of 256; otherwise its whole waves go to blocks of 64 vectors whose four
+// waves share the chunk's coordinates (project_narrow_kernel), and a last part of at most 48 vectors
+// goes to the lanes-over-coordinates kernel, where every lane works whatever the count is -- unless the
+// chunks, which all launches of a plan share, are shorter than 32 tiles: that kernel needs long chunks,
+// and then (or above 48 vectors) the last part gets a block of 64 of its own.
+constexpr uint32_t kRestFullTile = 192;
+constexpr uint32_t kTailMax = 48;
+constexpr uint64_t kTailMinTilesPerChunk = 32;
 
 constexpr uint64_t kSmallMaxD = 65536;      // kPlanSmall: a thread's fp32 chain stays <= 256 terms
 constexpr uint32_t kSmallMaxClients = 8;
@@ -120,7 +129,7 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
     if (d == 0 || d > kMaxD || m == 0 || m > kMaxM || n == 0 || n > kMaxN) return false;
     const uint64_t tiles_total = ceil_div(d, kTile);
     const bool small_ok = allow_qmode && n <= kSmallMaxClients && d <= kSmallMaxD && m <= 0x7fffffffu;
-    const bool little_work = m < 64 || ceil_div(m, 64) * tiles_total <= 1024;
+    const bool little_work = ceil_div(m, 64) * tiles_total <= 1024;   // fewer than 1024 wave-tiles in all
     const bool force_vectors = forced == kVariantValu || forced == kVariantMfma || !allow_qmode;
     const uint32_t full_tiles = m / kThreads, rem = m % kThreads;
     p.small_threads = 0;
@@ -128,6 +137,7 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
     p.wide = false;
     p.tail_begin = m;
     p.tail_groups = 0;
+    p.narrow_tiles = 0;
     if (!force_vectors && small_ok && (forced == kVariantSmall || (forced == kVariantAuto && little_work))) {
         // one Philox block per thread where d allows it: the serial chain of a thread is what a
         // launch-bound round waits for
@@ -140,14 +150,31 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
         p.tiles_per_chunk = (uint32_t)ceil_div(ceil_div(d, 4), threads);
     } else {
         // which vectors go to which kernel
-        bool coords_all = false, tail = false;
+        bool coords_all = false;
+        uint32_t main_tiles = (uint32_t)ceil_div(m, kThreads), narrow = 0, qvectors = 0;
+        // chunk length for about 8192 blocks in the launch of the 256-vector tiles, or in the launch of
+        // the 64-vector tiles when there is no other
+        auto chunk_tiles = [&](uint32_t mt, uint32_t nw) {
+            uint64_t want = ceil_div(kTargetBlocks, mt ? mt : (nw ? nw : 1u));
+            if (want < 1) want = 1;
+            if (want > tiles_total) want = tiles_total;
+            return ceil_div(tiles_total, want);
+        };
         if (!force_vectors) {
             if (forced == kVariantQ || forced == kVariantSmall) coords_all = true;
-            else coords_all = little_work || (full_tiles == 0 && rem <= kTailMax);
-            tail = !coords_all && full_tiles > 0 && rem > 0 && rem <= kTailMax;
+            else coords_all = little_work || m <= kTailMax;
+            if (!coords_all && rem > 0 && rem <= kRestFullTile) {
+                main_tiles = full_tiles;
+                narrow = rem / 64;
+                qvectors = rem % 64;
+                if (qvectors > kTailMax || (qvectors > 0 && chunk_tiles(main_tiles, narrow) < kTailMinTilesPerChunk)) {
+                    narrow += 1;
+                    qvectors = 0;
+                }
+            }
         }
+        if (coords_all) qvectors = m;
         const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
-        const uint32_t qvectors = coords_all ? m : (tail ? rem : 0);
         if (qvectors) {
             // 8 vectors per block share every load of G when there is enough work to fill the chip
             // with such blocks; 4 otherwise (more, shorter blocks)
@@ -158,6 +185,8 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
             p.tail_begin = m - qvectors;
             p.tail_groups = (uint32_t)ceil_div(qvectors, p.qj);
         }
+        const bool tail = !coords_all && qvectors > 0;
+        p.narrow_tiles = narrow;
         if (coords_all) {
             p.mode = kPlanCoords;
             p.jtiles = 0;
@@ -170,11 +199,8 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
             p.nchunks = (uint32_t)ceil_div(qtiles, tpcq);
         } else {
             p.mode = kPlanVectors;
-            p.jtiles = tail ? full_tiles : (uint32_t)ceil_div(m, kThreads);
-            uint64_t want = ceil_div(kTargetBlocks, p.jtiles);
-            if (want < 1) want = 1;
-            if (want > tiles_total) want = tiles_total;
-            uint64_t tpc = ceil_div(tiles_total, want);
+            p.jtiles = main_tiles;
+            uint64_t tpc = chunk_tiles(main_tiles, narrow);
 #ifdef CORE_EXPERIMENT
             if (const char* e = getenv("CORE_TPC")) tpc = strtoull(e, nullptr, 10);
 #endif
@@ -193,18 +219,19 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
                     tpc = tpc_wide;
                 }
             }
-            if (tail) {   // both kernels must cut d at the same places: whole 1024-coordinate tiles
-                tpc = ceil_div(tpc, 4) * 4;
-                if (tpc > 4 * kQTilesPerChunkMax) tpc = 4 * kQTilesPerChunkMax;
-            }
+            if (tail) tpc = ceil_div(tpc, 4) * 4;   // the lanes-over-coordinates kernel walks whole 1024-coordinate tiles
+            // both side kernels add one fp32 sum per step of at most 1024 coordinates into the chunk
+            // sum: keep that chain no longer than the main kernel's
+            if ((tail || narrow) && tpc > 4 * kQTilesPerChunkMax) tpc = 4 * kQTilesPerChunkMax;
             p.tiles_per_chunk = (uint32_t)tpc;
             p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
         }
     }
     // one block per (chunk, vector tile or group): both grids must stay valid launches
     const uint64_t chunk_slots = ceil_div(p.nchunks, 8) * 8;
-    const uint64_t grid = p.mode == kPlanSmall ? (uint64_t)p.jtiles
-                                               : chunk_slots * (p.jtiles > p.tail_groups ? p.jtiles : p.tail_groups);
+    uint64_t widest = p.jtiles > p.tail_groups ? p.jtiles : p.tail_groups;
+    if (p.narrow_tiles > widest) widest = p.narrow_tiles;
+    const uint64_t grid = p.mode == kPlanSmall ? (uint64_t)p.jtiles : chunk_slots * widest;
     if (grid > kMaxGridBlocks) return false;
     uint32_t Z = p.nchunks / 128u;
     if (Z < 1) Z = 1;
@@ -285,6 +312,14 @@ hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t 
 }
 
 bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+template <int NC>
+hipError_t launch_project_narrow(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+{
+    const dim3 g(blocks), b(kThreads);
+    return bf16 ? launch(project_narrow_kernel<NC, true>, g, b, st, a)
+                : launch(project_narrow_kernel<NC, false>, g, b, st, a);
+}
 
 template <int NC>
 hipError_t launch_project(const ProjectArgs& a, bool bf16, bool store_xi, uint32_t blocks, hipStream_t st)
@@ -437,7 +472,24 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
         if (e != hipSuccess) return hip_fail(e);
     }
     }
-    if (plan.tail_groups > 0) {   // lanes-over-coordinates kernel: all vectors, or the last m mod 256
+    if (plan.narrow_tiles > 0) {   // 64-vector blocks of the lanes-over-vectors kernel: whole waves of the rest
+        ProjectArgs w = a;
+        w.jtiles = plan.narrow_tiles;
+        w.j_begin = plan.jtiles * (uint32_t)kThreads;
+        const uint32_t blocks = chunk_slots * plan.narrow_tiles;
+        for (uint32_t c0 = 0; c0 < n; c0 += kMaxClientsPerPass) {
+            const uint32_t nc = (n - c0 < kMaxClientsPerPass) ? (n - c0) : kMaxClientsPerPass;
+            w.c0 = c0; w.nc = nc;
+            hipError_t e;
+            if (nc <= 1)      e = launch_project_narrow<1>(w, bf16, blocks, st);
+            else if (nc <= 2) e = launch_project_narrow<2>(w, bf16, blocks, st);
+            else if (nc <= 4) e = launch_project_narrow<4>(w, bf16, blocks, st);
+            else if (nc <= 8) e = launch_project_narrow<8>(w, bf16, blocks, st);
+            else              e = launch_project_narrow<16>(w, bf16, blocks, st);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+    }
+    if (plan.tail_groups > 0) {   // lanes-over-coordinates kernel: all vectors, or the last m mod 64
         ProjectArgs q = a;
         q.jtiles = plan.tail_groups;
         q.j_begin = plan.tail_begin;
@@ -959,7 +1011,7 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
     return enqueue_reconstruct_xi(d, m, pbar, 1.0f / (float)m, xi, gtilde, (hipStream_t)stream);
 }
 
-int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[8])
+int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[10])
 {
     Plan p;
     if (!plan || !make_plan(d, m, n, true, p)) return CORE_ERR_INVALID_ARGUMENT;
@@ -972,6 +1024,8 @@ int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[8])
     plan[5] = p.mode == kPlanSmall ? (uint64_t)p.jtiles : chunk_slots * plan[1];
     plan[6] = p.mode == kPlanVectors ? (uint64_t)(m - p.tail_begin) : 0;
     plan[7] = p.qj;
+    plan[8] = p.narrow_tiles;
+    plan[9] = 0;
     return CORE_OK;
 }
 

@@ -152,6 +152,104 @@ __global__ void __launch_bounds__(kThreads) project_kernel(ProjectArgs a)
     }
 }
 
+// The lanes-over-vectors projection for 64 vectors per block instead of 256: serves the whole waves
+// of a vector count that does not fill a tile of 256 (the rest m mod 256).  A wave of project_kernel is
+// latency-bound on its own (the generator is one long dependency chain) and only about 8 busy waves per
+// SIMD saturate the issue port, so a block of 256 with idle waves wastes wave slots.  Here all four
+// waves of a block take the SAME 64 vectors, a.j_begin + 64 jt + lane, and share the chunk's
+// coordinates instead: the chunk is walked in steps of 64 coordinates and wave w takes the steps
+// w, w + 4, w + 8, ...; each wave stages its own step of G in its own part of LDS, and the four
+// partial sums are added in wave order at the end, so the block writes one partial sum per (vector,
+// client) exactly like a block of project_kernel.  a.jtiles counts tiles of 64 vectors here.
+// Inside the loop the waves do not wait for each other: a wave's part of LDS is written and read by
+// that wave alone, and the LDS operations of one wave are performed in program order.
+constexpr int kNarrow = 64;
+
+template <int NC, bool BF16>
+__global__ void __launch_bounds__(kThreads) project_narrow_kernel(ProjectArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float tile[kThreads / 64][NC][kNarrow];
+    __shared__ float red[kThreads / 64][NC][kNarrow];
+
+    const uint32_t b = blockIdx.x;
+    const uint32_t xcd = b & 7u;
+    const uint32_t s = b >> 3;
+    const uint32_t chunk = (s / a.jtiles) * 8u + xcd;
+    const uint32_t jt = s % a.jtiles;
+    if (chunk >= a.nchunks) return;
+
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    const uint32_t w = (uint32_t)__builtin_amdgcn_readfirstlane((int)(t >> 6));   // wave-uniform, so scalar
+    const uint32_t j = a.j_begin + jt * kNarrow + lane;
+
+    constexpr uint32_t kStepsPerTile = kTile / kNarrow;
+    const uint64_t steps_total = (a.d + kNarrow - 1) / kNarrow;
+    const uint64_t step_begin = (uint64_t)chunk * a.tiles_per_chunk * kStepsPerTile;
+    uint64_t step_end = step_begin + (uint64_t)a.tiles_per_chunk * kStepsPerTile;
+    if (step_end > steps_total) step_end = steps_total;
+
+    Generator<3, 4> gen;
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
+
+    float acc_outer[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc_outer[c] = 0.0f;
+
+    // register prefetch of this wave's next step: lane l holds coordinate 64 step + l of every client
+    float pre[NC];
+    auto fetch = [&](uint64_t step) {
+        const uint64_t i = step * kNarrow + lane;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            float v = 0.0f;
+            if (step < step_end && i < a.d && (uint32_t)c < a.nc) v = load_g<BF16>(a.G, (uint64_t)(a.c0 + c) * a.ld + i);
+            pre[c] = v;
+        }
+    };
+    fetch(step_begin + w);
+
+    for (uint64_t step = step_begin + w; step < step_end; step += 4) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c = 0; c < NC; ++c) tile[w][c][lane] = pre[c];
+        __builtin_amdgcn_wave_barrier();
+        fetch(step + 4);
+
+        float acc[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
+        const uint32_t q0 = (uint32_t)(step * (kNarrow / 4));
+#pragma unroll 2
+        for (int qq = 0; qq < kNarrow / 4; ++qq) {
+            float z0, z1, z2, z3;
+            gen.block(q0 + (uint32_t)qq, j, z0, z1, z2, z3);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 g = *reinterpret_cast<const float4*>(&tile[w][c][4 * qq]);
+                acc[c] = fmaf(z0, g.x, acc[c]);
+                acc[c] = fmaf(z1, g.y, acc[c]);
+                acc[c] = fmaf(z2, g.z, acc[c]);
+                acc[c] = fmaf(z3, g.w, acc[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc_outer[c] += acc[c];
+    }
+
+#pragma unroll
+    for (int c = 0; c < NC; ++c) red[w][c][lane] = acc_outer[c];
+    __syncthreads();
+    if (w == 0 && j < a.m) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if ((uint32_t)c < a.nc) {
+                const float tot = ((red[0][c][lane] + red[1][c][lane]) + red[2][c][lane]) + red[3][c][lane];
+                a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + j] = kXiScale * tot;
+            }
+        }
+    }
+}
+
 // Matrix-pipe variant of the projection, used for passes of more than 8 clients (and selectable
 // with the environment variable CORE_PROJECT_VARIANT=mfma|valu for A/B runs).  Same lane mapping and generator as
 // project_kernel; the 4*NC v_fmac per call are replaced by NC v_mfma_f32_4x4x1_16B_f32: block

@@ -7,7 +7,7 @@
 #include "core.h"
 int main(void) {
     float dummy[64];
-    uint64_t plan[8];
+    uint64_t plan[10];
     unsigned long long acc = 0;
     for (uint64_t d = 1; d <= (1ull << 34); d = d * 3 + 1)
         for (uint32_t m = 1; m < (1u << 22); m = m * 5 + 3)

@@ -113,7 +113,7 @@ def test_vector_count_limit():
         assert L.core_reconstruct_update_batched(1, 0, 4, m, 1, FAKE, 1 << 32, 0.25, 0.1, FAKE + (1 << 40), None, 4,
                                                  None) == E.ERR_INVALID_ARGUMENT
         assert L.core_reconstruct_from_xi(4, m, FAKE, 0.1, FAKE + 64, 1 << 40, FAKE + 128, None) == E.ERR_INVALID_ARGUMENT
-        out = (ctypes.c_uint64 * 8)()
+        out = (ctypes.c_uint64 * 10)()
         assert L.core_debug_plan(4, m, 1, out) == E.ERR_INVALID_ARGUMENT
     # the largest accepted count passes validation (it then needs a device, or a workspace nobody has)
     assert core.core_workspace_bytes(4, top, 1) > 0
@@ -384,23 +384,30 @@ def test_launch_plan_invariants():
             threads = -(-nblk // p["tiles_per_chunk"])
             assert p["tiles_per_chunk"] <= 16 and threads <= 1024   # fp32 chain of a thread: <= 64 terms
             return
+        tiles_c = p["tiles_per_chunk"]
         if p["mode"] == 1:
-            tile, per_j, covered = 1024, p["vectors_per_block"], m
-            assert per_j in (4, 8) and p["tail_vectors"] == 0
-            assert p["tiles_per_chunk"] <= 64
+            assert p["vectors_per_block"] in (4, 8) and p["tail_vectors"] == 0 and p["narrow_tiles"] == 0
+            assert tiles_c <= 64
+            tiles = -(-d // 1024)
+            assert (p["jtiles"] - 1) * p["vectors_per_block"] < m <= p["jtiles"] * p["vectors_per_block"]
         else:
-            tile, per_j = 256, 256
-            assert p["tiles_per_chunk"] <= 1024
-            # the last m mod 256 vectors may go to a second, lanes-over-coordinates launch
-            tail = p["tail_vectors"]
-            covered = m - tail
-            if tail:
-                assert 0 < tail == m % 256 <= 160 and p["vectors_per_block"] in (4, 8)
-                assert p["tiles_per_chunk"] % 4 == 0 and covered % 256 == 0 and covered > 0
-                assert -(-tail // p["vectors_per_block"]) * -(-p["nchunks"] // 8) * 8 < (1 << 31)
-        tiles = -(-d // tile)
-        assert (p["nchunks"] - 1) * p["tiles_per_chunk"] < tiles <= p["nchunks"] * p["tiles_per_chunk"]
-        assert (p["jtiles"] - 1) * per_j < covered <= p["jtiles"] * per_j
+            assert tiles_c <= 1024
+            tiles = -(-d // 256)
+            # the rest m mod 256 may go to one-wave blocks of 64 vectors and, its last few vectors, to
+            # a lanes-over-coordinates launch; together the three launches cover every vector once
+            tail, narrow = p["tail_vectors"], p["narrow_tiles"]
+            if tail == 0 and narrow == 0:
+                assert (p["jtiles"] - 1) * 256 < m <= p["jtiles"] * 256
+            else:
+                rest = m - 256 * p["jtiles"]
+                assert 0 < rest <= 192 and rest == m % 256 and 0 <= tail <= 48 and narrow <= 3
+                assert 64 * (narrow - 1) < rest - tail <= 64 * narrow
+                assert tiles_c <= 256
+                if tail:
+                    assert p["vectors_per_block"] in (4, 8) and tiles_c % 4 == 0
+                chunk_slots = -(-p["nchunks"] // 8) * 8
+                assert chunk_slots * max(narrow, -(-tail // 4)) < (1 << 31)
+        assert (p["nchunks"] - 1) * tiles_c < tiles <= p["nchunks"] * tiles_c
         assert p["nchunks"] * p["jtiles"] <= p["blocks"] < (1 << 31)
         assert 1 <= p["slices"] <= 16
         assert ws >= 4 * p["nchunks"] * n * m + 8 * p["slices"] * n * m
@@ -409,28 +416,32 @@ def test_launch_plan_invariants():
     # the headline shapes keep the plan the profiles were taken with
     assert core.core_debug_plan(25_557_032, 1024, 8) == {
         "mode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160,
-        "tail_vectors": 0, "vectors_per_block": 0}
+        "tail_vectors": 0, "vectors_per_block": 0, "narrow_tiles": 0}
     p5 = core.core_debug_plan(124_439_808, 4096, 16)
     assert (p5["mode"], p5["jtiles"], p5["tiles_per_chunk"]) == (0, 16, 950)
     # the two launch-bound shapes take the one-launch plan, one Philox block per thread
     assert core.core_debug_plan(1024, 16, 4) == {
         "mode": 2, "jtiles": 16, "nchunks": 1, "tiles_per_chunk": 1, "slices": 1, "blocks": 16,
-        "tail_vectors": 0, "vectors_per_block": 0}
+        "tail_vectors": 0, "vectors_per_block": 0, "narrow_tiles": 0}
     assert core.core_debug_plan(4096, 64, 8)["mode"] == 2
     assert core.core_debug_plan(4096, 64, 9)["mode"] == 1          # more than 8 clients
     assert core.core_debug_plan(1 << 20, 16, 4)["mode"] == 1       # few vectors, long gradient
-    # up to 160 vectors on a long gradient: lanes over coordinates, 8 vectors per block
-    p160 = core.core_debug_plan(25_557_032, 160, 8)
-    assert (p160["mode"], p160["jtiles"], p160["vectors_per_block"]) == (1, 20, 8)
-    assert core.core_debug_plan(25_557_032, 161, 8)["mode"] == 0
-    # ragged vector counts: whole tiles of 256 to the lanes-over-vectors kernel, a short rest to the other
-    p320 = core.core_debug_plan(25_557_032, 320, 8)
-    assert (p320["mode"], p320["jtiles"], p320["tail_vectors"], p320["tiles_per_chunk"] % 4) == (0, 1, 64, 0)
-    p1000 = core.core_debug_plan(25_557_032, 1000, 8)     # 3 x 256 + 232: the rest fills a block well enough
-    assert (p1000["jtiles"], p1000["tail_vectors"]) == (4, 0)
+    # up to 48 vectors on a long gradient: lanes over coordinates, 8 vectors per block
+    p48 = core.core_debug_plan(25_557_032, 48, 8)
+    assert (p48["mode"], p48["jtiles"], p48["vectors_per_block"]) == (1, 6, 8)
+    # vector counts that do not fill tiles of 256: whole waves to blocks of 64 vectors; a short rest to the
+    # lanes-over-coordinates kernel where the chunks are long enough for it, else one more block of 64;
+    # more than 192 to one more tile of 256
+    def split(m):
+        p = core.core_debug_plan(25_557_032, m, 8)
+        return (p["mode"], p["jtiles"], p["narrow_tiles"], p["tail_vectors"])
+    assert split(49) == (0, 0, 1, 0) and split(64) == (0, 0, 1, 0) and split(100) == (0, 0, 2, 0)
+    assert split(128) == (0, 0, 2, 0) and split(192) == (0, 0, 3, 0) and split(193) == (0, 1, 0, 0)
+    assert split(320) == (0, 1, 1, 0) and split(300) == (0, 1, 1, 0) and split(1000) == (0, 4, 0, 0)
+    assert split(1088) == (0, 4, 1, 0) and split(1100) == (0, 4, 1, 12) and split(1024 + 190) == (0, 4, 3, 0)
     # sizes whose grid would not be launchable are refused up front
     import ctypes
-    out = (ctypes.c_uint64 * 8)()
+    out = (ctypes.c_uint64 * 10)()
     L = core.load_library()
     assert L.core_debug_plan(1 << 34, (1 << 32) - 1, 1, out) == binding.ERR_INVALID_ARGUMENT
     assert core.core_workspace_bytes(1 << 34, (1 << 32) - 1, 1) == 0

@@ -459,22 +459,26 @@ def test_streams_and_graph_capture():
 
 
 @pytest.mark.parametrize("d,m,n,bf16", [
-    (60000, 320, 8, False),     # 256 vectors to the lanes-over-vectors kernel + 64 to the lanes-over-coordinates one
-    (40000, 600, 3, True),      # 512 + 88
+    (60000, 320, 8, False),     # 256 vectors in a block of four waves + 64 in one-wave blocks
+    (40000, 600, 3, True),      # 512 + 64 + 24 by the lanes-over-coordinates kernel
     (53000, 257, 16, True),     # 256 on the matrix pipe + 1, the rest in two passes of 8 clients
-    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 76
-    (300000, 130, 2, False),    # fewer than 161 vectors on a long gradient: lanes over coordinates throughout
-    (66000, 200, 4, False),     # 200 vectors: one partly filled block of 256
+    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 64 in passes of 16 clients + 12
+    (300000, 130, 2, False),    # two one-wave blocks + 2
+    (66000, 200, 4, False),     # 200 vectors: one block of 256, all four waves busy
     (70001, 513, 2, False),     # 512 + 1
+    (270000, 49, 5, True),      # one wave, 49 of 64 lanes
+    (270000, 48, 5, True),      # lanes over coordinates throughout
+    (90000, 190, 20, False),    # three one-wave blocks (the last with 62 lanes), 20 clients in passes of 16
+    (40000, 447, 7, True),      # 256 + 3 x 64 (191 = 2 x 64 + 63: the 63 get a wave of their own)
 ])
-def test_ragged_vector_counts_split_between_the_two_projections(d, m, n, bf16):
+def test_ragged_vector_counts_split_between_the_projections(d, m, n, bf16):
     """Vector counts that are not multiples of 256, on shapes with enough work for the
-    lanes-over-vectors plan: the library's own choice gives the whole tiles to that kernel and a short
-    rest to the lanes-over-coordinates kernel, both writing the same per-chunk partial sums."""
+    lanes-over-vectors plan: the library's own choice gives whole tiles of 256 to blocks of four
+    waves, whole waves of the rest to one-wave blocks and a short remainder to the lanes-over-coordinates
+    kernel; all launches write the same per-chunk partial sums."""
     plan = core.core_debug_plan(d, m, n)
     _say(f"ragged vector count d={d} m={m} n={n} bf16={bf16} plan={plan}")
-    if m % 256 and m % 256 <= 160 and m > 256:
-        assert plan["mode"] == 0 and plan["tail_vectors"] == m % 256
+    assert plan["mode"] in (0, 1)
     rng = np.random.default_rng(d + 3 * m + n)
     G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
     if bf16:
