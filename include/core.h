@@ -285,6 +285,26 @@ int core_round_trial(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
 int core_accept_trial(uint64_t d, float *f_cur, const float *f_trial,
                       float *x, const float *x_trial, int32_t *accepted, core_stream stream);
 
+/* ---- diagnostics from the privacy appendix ---------------------------------------------------
+ * The appendix on differential privacy writes one machine's message as p = C(a) = Xi a and shows
+ * (lemma on the law of C(a)) that p is N(0, |a|^2 I_m): an observer of the projections learns the
+ * norm of the gradient and nothing about its direction.  Two consequences are exported.
+ *
+ * core_projection_sqnorms: sq[c] = sum_j P[c][j]^2 for every machine c (fp64, fixed summation
+ *   order).  sq[c] / m is an unbiased estimate of |g_c|^2 with relative standard deviation
+ *   sqrt(2/m), and m * (sq[c]/m) / |g_c|^2 is chi-square with m degrees of freedom.
+ *   P [n][m] device fp32, row-major without padding, as core_compress_batched writes it (in);
+ *   sq [n] device fp64 (out), 8-byte aligned, must not overlap P.
+ *
+ * core_privacy_loss: the privacy loss of the proof of the privacy theorem for one released
+ *   message with squared norm sqnorm = |p|^2, when the two adjacent gradients have norms sigma1
+ *   and sigma2:  L = (sqnorm / 2) (1/sigma2^2 - 1/sigma1^2) + m ln(sigma2 / sigma1),
+ *   i.e. the log-ratio of the N(0, sigma1^2 I_m) and N(0, sigma2^2 I_m) densities at p.
+ *   Pure host arithmetic (fp64); loss is a host pointer.  sqnorm >= 0, sigma1, sigma2 > 0, all
+ *   finite, else CORE_ERR_INVALID_ARGUMENT. */
+int core_projection_sqnorms(uint32_t m, uint32_t n, const float *P, double *sq, core_stream stream);
+int core_privacy_loss(double sqnorm, uint32_t m, double sigma1, double sigma2, double *loss);
+
 /* ---- materialised-Xi comparison variant ---------------------------------------------------
  * The matrix Xi = [xi_1 ... xi_m]^T of the paper's privacy appendix (p = Xi a) is normally never
  * stored.  These entry points store it once, while projecting, and read it back to reconstruct,

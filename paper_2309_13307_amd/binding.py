@@ -30,6 +30,7 @@ EXPORTS = (
     "core_compress_batched", "core_reconstruct", "core_round", "core_debug_philox", "core_debug_xi",
     "core_xi_bytes", "core_compress_batched_store_xi", "core_reconstruct_from_xi",
     "core_round_materialized", "core_reconstruct_update", "core_round_update",
+    "core_projection_sqnorms", "core_privacy_loss",
     "core_nonconvex_step", "core_step_size_option2", "core_reconstruct_trial", "core_round_trial",
     "core_accept_trial", "core_debug_plan", "core_round_update_r", "core_advance_round",
     "core_round_trial_r", "core_reconstruct_update_batched", "core_build_id",
@@ -93,6 +94,10 @@ def load_library() -> ctypes.CDLL:
                                     vp, sz, vp]
     L.core_round_update.restype = i32
     f64 = ctypes.c_double
+    L.core_projection_sqnorms.argtypes = [u32, u32, vp, vp, vp]
+    L.core_projection_sqnorms.restype = i32
+    L.core_privacy_loss.argtypes = [f64, u32, f64, f64, ctypes.POINTER(ctypes.c_double)]
+    L.core_privacy_loss.restype = i32
     L.core_nonconvex_step.argtypes = [u64, u32, vp, f32, f64, f64, vp, vp, vp]
     L.core_nonconvex_step.restype = i32
     L.core_step_size_option2.argtypes = [u64, u32, f64, f64, f64, f64, ctypes.POINTER(f64)]
@@ -311,6 +316,25 @@ def core_step_size_option2(d: int, m: int, r1: float, H: float, L: float, Delta:
     out = ctypes.c_double(0.0)
     rc = load_library().core_step_size_option2(d, m, r1, H, L, Delta, ctypes.byref(out))
     _check(rc, "core_step_size_option2")
+    return out.value
+
+
+def core_projection_sqnorms(P: torch.Tensor, sq: torch.Tensor) -> None:
+    """sq[c] = sum_j P[c][j]^2 (fp64) for the projections P [n][m] of every machine."""
+    _require_cuda(P, sq)
+    if P.dim() != 2 or not P.is_contiguous() or P.dtype != torch.float32:
+        raise ValueError("P must be a contiguous fp32 [n][m] tensor")
+    if sq.dtype != torch.float64 or sq.numel() != P.shape[0] or not sq.is_contiguous():
+        raise ValueError("sq must be a contiguous fp64 tensor of n elements")
+    rc = load_library().core_projection_sqnorms(P.shape[1], P.shape[0], P.data_ptr(), sq.data_ptr(), _stream())
+    _check(rc, "core_projection_sqnorms")
+
+
+def core_privacy_loss(sqnorm: float, m: int, sigma1: float, sigma2: float) -> float:
+    """Privacy loss of one released message (privacy appendix; host arithmetic, fp64)."""
+    out = ctypes.c_double(0.0)
+    rc = load_library().core_privacy_loss(sqnorm, m, sigma1, sigma2, ctypes.byref(out))
+    _check(rc, "core_privacy_loss")
     return out.value
 
 

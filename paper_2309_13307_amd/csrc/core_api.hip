@@ -179,9 +179,6 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
             // 8 vectors per block share every load of G when there is enough work to fill the chip
             // with such blocks; 4 otherwise (more, shorter blocks)
             p.qj = (qvectors > 4 && ceil_div(qvectors, 8) * qtiles >= 2 * kBlockSlots) ? 8 : 4;
-#ifdef CORE_EXPERIMENT
-            if (const char* e = getenv("CORE_QJ")) p.qj = (uint32_t)strtoul(e, nullptr, 10) == 8 ? 8 : 4;
-#endif
             p.tail_begin = m - qvectors;
             p.tail_groups = (uint32_t)ceil_div(qvectors, p.qj);
         }
@@ -201,17 +198,9 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
             p.mode = kPlanVectors;
             p.jtiles = main_tiles;
             uint64_t tpc = chunk_tiles(main_tiles, narrow);
-#ifdef CORE_EXPERIMENT
-            if (const char* e = getenv("CORE_TPC")) tpc = strtoull(e, nullptr, 10);
-#endif
             if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
             // more than 32 clients: wide passes, if the shorter chunks they need still give a launchable grid
-#ifdef CORE_EXPERIMENT
-            const bool no_wide = getenv("CORE_NOWIDE") != nullptr;
-#else
-            const bool no_wide = false;
-#endif
-            if (n > kMaxClientsPerPassMfma && forced != kVariantValu && !no_wide) {
+            if (n > kMaxClientsPerPassMfma && forced != kVariantValu) {
                 const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
                 const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
                 if (ceil_div(chunks_wide, 8) * 8 * p.jtiles <= kMaxGridBlocks) {
@@ -563,9 +552,6 @@ int enqueue_reconstruct(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, c
     const uint64_t columns = ceil_div(nblk, 64);
     uint32_t split = 1;
     while (split < (uint32_t)kSplitMaxWaves && columns * split < kWaveSlots / 2 && 2 * split <= m) split *= 2;
-#ifdef CORE_EXPERIMENT
-    if (const char* ev = getenv("CORE_SPLIT")) split = (uint32_t)strtoul(ev, nullptr, 10);
-#endif
     if (!two && split >= 2) {
         const dim3 g((uint32_t)columns), b(64 * split);
         const size_t lds = (size_t)split * 4 * 64 * sizeof(float);
@@ -881,6 +867,26 @@ int core_step_size_option2(uint64_t d, uint32_t m, double r1, double H, double L
     const double second = std::pow(H, -0.5) * std::pow(L * Delta, -0.25) * std::pow((double)d, -0.75) *
                           std::pow((double)m, 0.75) / 1600.0;
     *h = first < second ? first : second;
+    return CORE_OK;
+}
+
+int core_projection_sqnorms(uint32_t m, uint32_t n, const float* P, double* sq, core_stream stream)
+{
+    if (!P || !sq || m == 0 || m > kMaxM || n == 0 || n > kMaxN) return CORE_ERR_INVALID_ARGUMENT;
+    if (intersects((const float*)sq, 2 * (uint64_t)n, P, (uint64_t)n * m)) return CORE_ERR_INVALID_ARGUMENT;
+    if (!aligned_to(P, 4) || !aligned_to(sq, 8)) return CORE_ERR_MISALIGNED;
+    const int rc = check_device();
+    if (rc != CORE_OK) return rc;
+    const hipError_t e = launch(projection_sqnorms_kernel, dim3(n), dim3(kThreads), (hipStream_t)stream, P, m, sq);
+    return e == hipSuccess ? CORE_OK : hip_fail(e);
+}
+
+int core_privacy_loss(double sqnorm, uint32_t m, double sigma1, double sigma2, double* loss)
+{
+    if (!loss || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
+    if (!(sqnorm >= 0.0) || !(sigma1 > 0.0) || !(sigma2 > 0.0)) return CORE_ERR_INVALID_ARGUMENT;
+    if (std::isinf(sqnorm) || std::isinf(sigma1) || std::isinf(sigma2)) return CORE_ERR_INVALID_ARGUMENT;
+    *loss = 0.5 * sqnorm * (1.0 / (sigma2 * sigma2) - 1.0 / (sigma1 * sigma1)) + (double)m * std::log(sigma2 / sigma1);
     return CORE_OK;
 }
 

@@ -1012,6 +1012,29 @@ __global__ void __launch_bounds__(kThreads) nonconvex_step_kernel(const float* p
     }
 }
 
+// Squared norms of the released projections (appendix on differential privacy, lemma on the law of
+// C(a)): sq[c] = sum_j P[c][j]^2.  C(a) is N(0, |a|^2 I_m), so sq[c] / m estimates |g_c|^2 and sq[c]
+// is all of P[c] that the privacy loss depends on.  One block per client; squares are summed in fp64
+// in a fixed order (thread-strided, then an LDS tree), as in nonconvex_step_kernel.
+__global__ void __launch_bounds__(kThreads) projection_sqnorms_kernel(const float* P, uint32_t m, double* sq)
+{
+    __shared__ double part[kThreads];
+    const uint32_t t = threadIdx.x;
+    const float* row = P + (uint64_t)blockIdx.x * m;
+    double s = 0.0;
+    for (uint32_t j = t; j < m; j += kThreads) {
+        const double v = (double)row[j];
+        s += v * v;
+    }
+    part[t] = s;
+    __syncthreads();
+    for (uint32_t w = kThreads / 2; w > 0; w >>= 1) {
+        if (t < w) part[t] += part[t + w];
+        __syncthreads();
+    }
+    if (t == 0) sq[blockIdx.x] = part[0];
+}
+
 // Comparison step of Algorithm 3, part 1: the decision (strict decrease; NaN rejects).
 __global__ void accept_decide_kernel(float* f_cur, const float* f_trial, int32_t* accepted)
 {
