@@ -48,11 +48,11 @@ OPS_GENERATE = 26
 # compiled kernels at those shapes: they are reported only while the kernel sources still hash to
 # `kernel_id`, and as null otherwise.
 COUNTERS = {
-    "kernel_id": "16cf18c6d4b234c3",
+    "kernel_id": "55bb963166ad31bb",
     "config4": {
         "source": "profiles/core_round_config4.md", "date": "2026-11-27",
-        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200635 * 2 * 1024, "write_bytes": 65216 * 1024},
-        "reconstruct": {"SQ_INSTS_VALU": 6.10726e9, "fetch_bytes": 42 * 2 * 1024, "write_bytes": 99832.2 * 1024},
+        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200632 * 2 * 1024, "write_bytes": 65216 * 1024},
+        "reconstruct": {"SQ_INSTS_VALU": 6.10726e9, "fetch_bytes": 41 * 2 * 1024, "write_bytes": 99832.2 * 1024},
     },
     "config5": {
         "source": "profiles/core_round_config5.md", "date": "2026-11-27",
