@@ -347,8 +347,10 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
  *   plan[4] slices of the cross-chunk sum
  *   plan[5] projection blocks launched per pass of clients (mode 0: by the 256-vector kernel)
  *   Mode 0 serves the rest m mod 256, when it is at most 192, without half-empty blocks of 256:
- *   plan[8] one-wave blocks of 64 vectors that follow the tiles of 256 (a second launch), and
- *   plan[6] the last vectors (at most 48) projected by a lanes-over-coordinates launch instead;
+ *   plan[8] tiles of 64 vectors that follow the tiles of 256 (a second launch: blocks whose four waves
+ *           share the chunk's coordinates), and
+ *   plan[6] the last vectors (at most 48) projected by a lanes-over-coordinates launch instead, which
+ *           happens only where the chunks are at least 32 tiles long;
  *   plan[7] vectors per block of the lanes-over-coordinates kernel (4 or 8; 0 if it is not used)
  *   plan[9] reserved (0)
  * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */

@@ -154,12 +154,26 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
         uint32_t main_tiles = (uint32_t)ceil_div(m, kThreads), narrow = 0, qvectors = 0;
         // chunk length for about 8192 blocks in the launch of the 256-vector tiles, or in the launch of
         // the 64-vector tiles when there is no other
-        auto chunk_tiles = [&](uint32_t mt, uint32_t nw) {
+        // More than 32 clients: wide passes for the 256-vector tiles, with chunks of at most 16 tiles, if
+        // those shorter chunks still give a launchable grid.
+        auto chunk_tiles = [&](uint32_t mt, uint32_t nw, bool& wide) {
             uint64_t want = ceil_div(kTargetBlocks, mt ? mt : (nw ? nw : 1u));
             if (want < 1) want = 1;
             if (want > tiles_total) want = tiles_total;
-            return ceil_div(tiles_total, want);
+            uint64_t tpc = ceil_div(tiles_total, want);
+            if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
+            wide = false;
+            if (mt > 0 && n > kMaxClientsPerPassMfma && forced != kVariantValu) {
+                const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
+                const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
+                if (ceil_div(chunks_wide, 8) * 8 * mt <= kMaxGridBlocks) {
+                    wide = true;
+                    tpc = tpc_wide;
+                }
+            }
+            return tpc;
         };
+        bool wide = false;
         if (!force_vectors) {
             if (forced == kVariantQ || forced == kVariantSmall) coords_all = true;
             else coords_all = little_work || m <= kTailMax;
@@ -167,7 +181,7 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
                 main_tiles = full_tiles;
                 narrow = rem / 64;
                 qvectors = rem % 64;
-                if (qvectors > kTailMax || (qvectors > 0 && chunk_tiles(main_tiles, narrow) < kTailMinTilesPerChunk)) {
+                if (qvectors > kTailMax || (qvectors > 0 && chunk_tiles(main_tiles, narrow, wide) < kTailMinTilesPerChunk)) {
                     narrow += 1;
                     qvectors = 0;
                 }
@@ -197,17 +211,8 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
         } else {
             p.mode = kPlanVectors;
             p.jtiles = main_tiles;
-            uint64_t tpc = chunk_tiles(main_tiles, narrow);
-            if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
-            // more than 32 clients: wide passes, if the shorter chunks they need still give a launchable grid
-            if (n > kMaxClientsPerPassMfma && forced != kVariantValu) {
-                const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
-                const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
-                if (ceil_div(chunks_wide, 8) * 8 * p.jtiles <= kMaxGridBlocks) {
-                    p.wide = true;
-                    tpc = tpc_wide;
-                }
-            }
+            uint64_t tpc = chunk_tiles(main_tiles, narrow, wide);
+            p.wide = wide;
             if (tail) tpc = ceil_div(tpc, 4) * 4;   // the lanes-over-coordinates kernel walks whole 1024-coordinate tiles
             // both side kernels add one fp32 sum per step of at most 1024 coordinates into the chunk
             // sum: keep that chain no longer than the main kernel's

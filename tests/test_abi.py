@@ -393,8 +393,8 @@ def test_launch_plan_invariants():
         else:
             assert tiles_c <= 1024
             tiles = -(-d // 256)
-            # the rest m mod 256 may go to one-wave blocks of 64 vectors and, its last few vectors, to
-            # a lanes-over-coordinates launch; together the three launches cover every vector once
+            # the rest m mod 256 may go to tiles of 64 vectors and, its last few vectors, to a
+            # lanes-over-coordinates launch; together the three launches cover every vector once
             tail, narrow = p["tail_vectors"], p["narrow_tiles"]
             if tail == 0 and narrow == 0:
                 assert (p["jtiles"] - 1) * 256 < m <= p["jtiles"] * 256
@@ -404,7 +404,7 @@ def test_launch_plan_invariants():
                 assert 64 * (narrow - 1) < rest - tail <= 64 * narrow
                 assert tiles_c <= 256
                 if tail:
-                    assert p["vectors_per_block"] in (4, 8) and tiles_c % 4 == 0
+                    assert p["vectors_per_block"] in (4, 8) and tiles_c % 4 == 0 and tiles_c >= 32
                 chunk_slots = -(-p["nchunks"] // 8) * 8
                 assert chunk_slots * max(narrow, -(-tail // 4)) < (1 << 31)
         assert (p["nchunks"] - 1) * tiles_c < tiles <= p["nchunks"] * tiles_c

@@ -117,6 +117,33 @@ def test_resnet50_size_with_50_clients_sampled():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.timeout(300)
+def test_resnet50_size_with_a_vector_count_split_over_three_launches():
+    """m = 1108 at the ResNet-50 size: four tiles of 256 vectors, one tile of 64 and the last 20 vectors
+    by the lanes-over-coordinates kernel (which only long chunks admit, so small shapes never take
+    that path); 4 clients.  Sampled vectors from each of the three parts over the full d, and sampled
+    coordinate blocks over all m."""
+    case = workloads.config4(DEV, m=1108, n=4)
+    plan = core.core_debug_plan(case.d, case.m, case.n)
+    _say(f"config4 shape with m={case.m} n={case.n}: plan {plan}")
+    assert (plan["mode"], plan["jtiles"], plan["narrow_tiles"], plan["tail_vectors"]) == (0, 4, 1, 20)
+    ws = core.alloc_workspace(case.d, case.m, case.n)
+    P, pbar = core.core_compress_batched(case.seed, 1, case.G, case.m, ws=ws)
+    pbar2, gtilde = core.core_round(case.seed, 1, case.G, case.m, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(pbar, pbar2)
+    assert bool(torch.isfinite(gtilde).all())
+    jidx = np.array([0, 255, 256, 1023, 1024, 1025, 1060, 1087, 1088, 1089, 1095, 1096, 1103, 1104, 1107],
+                    dtype=np.uint32)
+    G_host = workloads.to_host(case.G)
+    _sampled_check(case, 1, pbar, gtilde, jidx, 1024, "config4 m=1108", G_host=G_host)
+    P_ref = _oracle_columns(case.seed, 1, G_host, jidx)
+    norms = np.array([float(torch.linalg.vector_norm(case.G[c].double())) for c in range(case.n)])
+    parity.check_projections(P.cpu().numpy()[:, jidx], P_ref, norms, case.d, case.m, "config4 m=1108 P")
+    del case, G_host
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.timeout(900)
 def test_config5_full_size_sampled():
     case = workloads.config5(DEV)

@@ -459,23 +459,24 @@ def test_streams_and_graph_capture():
 
 
 @pytest.mark.parametrize("d,m,n,bf16", [
-    (60000, 320, 8, False),     # 256 vectors in a block of four waves + 64 in one-wave blocks
-    (40000, 600, 3, True),      # 512 + 64 + 24 by the lanes-over-coordinates kernel
+    (60000, 320, 8, False),     # one tile of 256 vectors + one tile of 64
+    (40000, 600, 3, True),      # 512 + 64 + 24 in a tile of 64 of their own (short chunks)
     (53000, 257, 16, True),     # 256 on the matrix pipe + 1, the rest in two passes of 8 clients
-    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 64 in passes of 16 clients + 12
-    (300000, 130, 2, False),    # two one-wave blocks + 2
+    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 64 + 12, the tiles of 64 in passes of 16 clients
+    (300000, 130, 2, False),    # two tiles of 64 + 2 in a third
     (66000, 200, 4, False),     # 200 vectors: one block of 256, all four waves busy
     (70001, 513, 2, False),     # 512 + 1
-    (270000, 49, 5, True),      # one wave, 49 of 64 lanes
+    (270000, 49, 5, True),      # one tile of 64, 49 of 64 lanes
     (270000, 48, 5, True),      # lanes over coordinates throughout
-    (90000, 190, 20, False),    # three one-wave blocks (the last with 62 lanes), 20 clients in passes of 16
-    (40000, 447, 7, True),      # 256 + 3 x 64 (191 = 2 x 64 + 63: the 63 get a wave of their own)
+    (90000, 190, 20, False),    # three tiles of 64 (the last with 62 lanes), 20 clients in passes of 16
+    (40000, 447, 7, True),      # 256 + 3 x 64 (191 = 2 x 64 + 63: the 63 get a tile of their own)
 ])
 def test_ragged_vector_counts_split_between_the_projections(d, m, n, bf16):
     """Vector counts that are not multiples of 256, on shapes with enough work for the
     lanes-over-vectors plan: the library's own choice gives whole tiles of 256 to blocks of four
-    waves, whole waves of the rest to one-wave blocks and a short remainder to the lanes-over-coordinates
-    kernel; all launches write the same per-chunk partial sums."""
+    waves, whole waves of the rest to blocks of 64 vectors whose waves share the chunk, and a short
+    remainder to one more such block (the lanes-over-coordinates kernel takes it only where chunks are
+    long: that path is covered at full size); all launches write the same per-chunk partial sums."""
     plan = core.core_debug_plan(d, m, n)
     _say(f"ragged vector count d={d} m={m} n={n} bf16={bf16} plan={plan}")
     assert plan["mode"] in (0, 1)
