@@ -35,6 +35,11 @@ int main(void) {
     double h = 0; rc = core_step_size_option2(1 << 20, 64, 2.0, 0.1, 3.0, 4.0, &h);
     printf("opt2 rc %d h %g acc %llu\n", rc, h, acc);
     if (rc != CORE_OK) return 6;
+    double loss = -1.0; rc = core_privacy_loss(32.0, 8, 2.0, 2.0, &loss);   /* equal norms: no loss */
+    if (rc != CORE_OK || loss != 0.0) return 9;
+    if (core_privacy_loss(32.0, 8, 2.0, 0.0, &loss) != CORE_ERR_INVALID_ARGUMENT) return 10;
+    /* the output must not overlap the projections */
+    if (core_projection_sqnorms(4, 2, dummy, (double *)(dummy + 6), NULL) != CORE_ERR_INVALID_ARGUMENT) return 11;
     puts("sanitized client ok");
     return 0;
 }
