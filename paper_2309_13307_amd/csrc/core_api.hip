@@ -422,49 +422,49 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
 
     const uint32_t chunk_slots = (uint32_t)(ceil_div(plan.nchunks, 8) * 8);
     if (plan.jtiles > 0) {   // lanes-over-vectors kernels: the tiles of 256 vectors
-    const uint32_t blocks = chunk_slots * plan.jtiles;
-    for (uint32_t c0 = 0; c0 < n;) {
-        const uint32_t left = n - c0;
-        const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
-        // Every pass regenerates the normals, so a pass takes as many clients as its kernel can
-        // hold: 64 on the wide matrix-pipe kernel when more than 32 are left (ResNet-50-sized
-        // gradient, m = 1024, projection alone: n = 50 in one pass 32.6 ms against 48.2 ms in passes
-        // of 32 + 18, n = 64 39.5 against 52.9 ms, n = 36 25.4 against 37.4 ms), 32 on the two-level
-        // matrix-pipe kernel, 16 on the VALU.
-        const bool mfma = !store && use_mfma_projection(left);
-        const bool wide = mfma && plan.wide && left > kMaxClientsPerPassMfma;
-        const uint32_t cap = wide ? kMaxClientsPerPassWide : mfma ? kMaxClientsPerPassMfma : kMaxClientsPerPass;
-        const uint32_t nc = left < cap ? left : cap;
-        a.c0 = c0; a.nc = nc;
-        c0 += nc;
-        hipError_t e;
-        if (wide) {
-            switch ((nc + 3) / 4) {   // client groups of 4: 9 to 16
-                case 9:  e = launch_project_mfma_wide<9>(a, bf16, blocks, st); break;
-                case 10: e = launch_project_mfma_wide<10>(a, bf16, blocks, st); break;
-                case 11: e = launch_project_mfma_wide<11>(a, bf16, blocks, st); break;
-                case 12: e = launch_project_mfma_wide<12>(a, bf16, blocks, st); break;
-                case 13: e = launch_project_mfma_wide<13>(a, bf16, blocks, st); break;
-                case 14: e = launch_project_mfma_wide<14>(a, bf16, blocks, st); break;
-                case 15: e = launch_project_mfma_wide<15>(a, bf16, blocks, st); break;
-                default: e = launch_project_mfma_wide<16>(a, bf16, blocks, st); break;
-            }
-        } else
-        if (mfma) {
-            if (nc <= 4)       e = launch_project_mfma<1>(a, bf16, blocks, st);
-            else if (nc <= 8)  e = launch_project_mfma<2>(a, bf16, blocks, st);
-            else if (nc <= 12) e = launch_project_mfma<3>(a, bf16, blocks, st);
-            else if (nc <= 16) e = launch_project_mfma<4>(a, bf16, blocks, st);
-            else if (nc <= 24) e = launch_project_mfma<6>(a, bf16, blocks, st);
-            else               e = launch_project_mfma<8>(a, bf16, blocks, st);
-        } else
-        if (nc <= 1)      e = launch_project<1>(a, bf16, store, blocks, st);
-        else if (nc <= 2) e = launch_project<2>(a, bf16, store, blocks, st);
-        else if (nc <= 4) e = launch_project<4>(a, bf16, store, blocks, st);
-        else if (nc <= 8) e = launch_project<8>(a, bf16, store, blocks, st);
-        else              e = launch_project<16>(a, bf16, store, blocks, st);
-        if (e != hipSuccess) return hip_fail(e);
-    }
+        const uint32_t blocks = chunk_slots * plan.jtiles;
+        for (uint32_t c0 = 0; c0 < n;) {
+            const uint32_t left = n - c0;
+            const bool store = (xi_store != nullptr) && c0 == 0;   // later passes regenerate, store once
+            // Every pass regenerates the normals, so a pass takes as many clients as its kernel can
+            // hold: 64 on the wide matrix-pipe kernel when more than 32 are left (ResNet-50-sized
+            // gradient, m = 1024, projection alone: n = 50 in one pass 32.6 ms against 48.2 ms in passes
+            // of 32 + 18, n = 64 39.5 against 52.9 ms, n = 36 25.4 against 37.4 ms), 32 on the two-level
+            // matrix-pipe kernel, 16 on the VALU.
+            const bool mfma = !store && use_mfma_projection(left);
+            const bool wide = mfma && plan.wide && left > kMaxClientsPerPassMfma;
+            const uint32_t cap = wide ? kMaxClientsPerPassWide : mfma ? kMaxClientsPerPassMfma : kMaxClientsPerPass;
+            const uint32_t nc = left < cap ? left : cap;
+            a.c0 = c0; a.nc = nc;
+            c0 += nc;
+            hipError_t e;
+            if (wide) {
+                switch ((nc + 3) / 4) {   // client groups of 4: 9 to 16
+                    case 9:  e = launch_project_mfma_wide<9>(a, bf16, blocks, st); break;
+                    case 10: e = launch_project_mfma_wide<10>(a, bf16, blocks, st); break;
+                    case 11: e = launch_project_mfma_wide<11>(a, bf16, blocks, st); break;
+                    case 12: e = launch_project_mfma_wide<12>(a, bf16, blocks, st); break;
+                    case 13: e = launch_project_mfma_wide<13>(a, bf16, blocks, st); break;
+                    case 14: e = launch_project_mfma_wide<14>(a, bf16, blocks, st); break;
+                    case 15: e = launch_project_mfma_wide<15>(a, bf16, blocks, st); break;
+                    default: e = launch_project_mfma_wide<16>(a, bf16, blocks, st); break;
+                }
+            } else
+            if (mfma) {
+                if (nc <= 4)       e = launch_project_mfma<1>(a, bf16, blocks, st);
+                else if (nc <= 8)  e = launch_project_mfma<2>(a, bf16, blocks, st);
+                else if (nc <= 12) e = launch_project_mfma<3>(a, bf16, blocks, st);
+                else if (nc <= 16) e = launch_project_mfma<4>(a, bf16, blocks, st);
+                else if (nc <= 24) e = launch_project_mfma<6>(a, bf16, blocks, st);
+                else               e = launch_project_mfma<8>(a, bf16, blocks, st);
+            } else
+            if (nc <= 1)      e = launch_project<1>(a, bf16, store, blocks, st);
+            else if (nc <= 2) e = launch_project<2>(a, bf16, store, blocks, st);
+            else if (nc <= 4) e = launch_project<4>(a, bf16, store, blocks, st);
+            else if (nc <= 8) e = launch_project<8>(a, bf16, store, blocks, st);
+            else              e = launch_project<16>(a, bf16, store, blocks, st);
+            if (e != hipSuccess) return hip_fail(e);
+        }
     }
     if (plan.narrow_tiles > 0) {   // 64-vector blocks of the lanes-over-vectors kernel: whole waves of the rest
         ProjectArgs w = a;
