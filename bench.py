@@ -249,20 +249,20 @@ def time_rounds(case, steps, warmup, graph=False, mat=False, first_round=0):
     }
 
 
-def other_workload(name, make, dev, steps, with_graph):
+def other_workload(name, make, dev, steps, warmup, with_graph):
     """Round time and whole-round fraction of the lane-op peak for one of the other configurations."""
     case = make(dev)
-    r = time_rounds(case, steps, 3)
+    r = time_rounds(case, steps, warmup)
     ops = r["ops_proj"] + r["ops_recon"]
     out = {
-        "d": case.d, "m": case.m, "n": case.n, "steps": steps,
+        "d": case.d, "m": case.m, "n": case.n, "steps": steps, "warmup": warmup,
         "ms_per_round": r["s_per_step"] * 1e3,
         "coords_per_s": case.d * case.m * case.n / r["s_per_step"],
         "whole_round_frac": ops / r["s_per_step"] / PEAK_LANE_OPS,
         "compress_ms": r["t_proj"] * 1e3, "reconstruct_ms": r["t_recon"] * 1e3,
     }
     if with_graph:
-        g = time_rounds(case, steps, 3, graph=True, first_round=r["next_round"])
+        g = time_rounds(case, steps, warmup, graph=True, first_round=r["next_round"])
         out["ms_per_round_graph_replay"] = g["s_per_step"] * 1e3
         out["whole_round_frac_graph_replay"] = ops / g["s_per_step"] / PEAK_LANE_OPS
     del case
@@ -408,9 +408,11 @@ def main():
         del case
         torch.cuda.empty_cache()
         others = {}
-        for name, steps, with_graph in (("config1", 200, True), ("config2", 200, True), ("config3", 30, True),
-                                        ("config5", 3, False)):
-            others[name] = other_workload(name, makers[name], dev, steps, with_graph)
+        # warm-up long enough for the clocks to settle: at config 3 three rounds are 1 ms of work, and the
+        # first 30 rounds after them run 10 % slower than the 200 that follow
+        for name, steps, warmup, with_graph in (("config1", 200, 50, True), ("config2", 200, 50, True),
+                                                ("config3", 200, 50, True), ("config5", 3, 1, False)):
+            others[name] = other_workload(name, makers[name], dev, steps, warmup, with_graph)
         out["other_workloads"] = others
     print(json.dumps(out))
     return 0
