@@ -337,7 +337,7 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
 
 /* The launch plan core_compress_batched / core_round would use for these sizes (host arithmetic,
  * nothing is launched; `plan` is a HOST pointer to 10 values):
- *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (at most 48
+ *   plan[0] 0 = lanes-over-vectors projection, 1 = lanes-over-coordinates projection (fewer than 5
  *           vectors, or little work), 2 = one workgroup per vector with the sums finished inside it (tiny
  *           problems with at most 8 clients and d <= 65536: projection, cross-chunk sum and client
  *           mean are then a single launch and the workspace is not used)
@@ -349,10 +349,9 @@ int core_round_materialized(uint64_t seed, uint64_t round, uint64_t d, uint32_t 
  *   Mode 0 serves the rest m mod 256, when it is at most 192, without half-empty blocks of 256:
  *   plan[8] tiles of 64 vectors that follow the tiles of 256 (a second launch: blocks whose four waves
  *           share the chunk's coordinates), and
- *   plan[6] the last vectors (at most 48) projected by a lanes-over-coordinates launch instead, which
- *           happens only where the chunks are at least 32 tiles long;
+ *   plan[6] tiles of plan[9] = 8, 16 or 32 vectors that follow those (a third launch of the same kernel
+ *           with the lanes of a wave split between vectors and Philox blocks; both 0 if there are none);
  *   plan[7] vectors per block of the lanes-over-coordinates kernel (4 or 8; 0 if it is not used)
- *   plan[9] reserved (0)
  * Returns CORE_ERR_INVALID_ARGUMENT for sizes out of range. */
 int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[10]);
 
@@ -370,6 +369,7 @@ int core_debug_philox(uint64_t seed, uint64_t round, uint32_t j, uint64_t q0, ui
  *   layout 2  the reconstruction kernels and the small-problem projection: lanes over blocks, the
  *             vector index wave-uniform
  *   layout 3  the generator of core_debug_xi
+ *   layout 4  the projection of tiles of fewer than 64 vectors: lanes over vectors and blocks at once
  * j0 + nj <= 2^32, q0 + nq <= 2^32, nj * nq <= 2^28.  out device uint32 [nj][nq][4]. */
 int core_debug_philox_layout(int layout, uint64_t seed, uint64_t round, uint32_t j0, uint32_t nj,
                              uint64_t q0, uint64_t nq, uint32_t *out, core_stream stream);

@@ -453,8 +453,8 @@ def core_debug_plan(d: int, m: int, n: int) -> dict:
     out = (ctypes.c_uint64 * 10)()
     rc = load_library().core_debug_plan(d, m, n, out)
     _check(rc, "core_debug_plan")
-    keys = ("mode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks", "tail_vectors", "vectors_per_block",
-            "narrow_tiles")
+    keys = ("mode", "jtiles", "nchunks", "tiles_per_chunk", "slices", "blocks", "sub_tiles", "vectors_per_block",
+            "narrow_tiles", "sub_tile_vectors")
     return dict(zip(keys, (int(v) for v in out)))
 
 
@@ -533,7 +533,7 @@ def core_debug_philox(seed: int, rnd: int, j: int, q0: int, nblocks: int, device
     return out
 
 
-PHILOX_LAYOUTS = {"scalar_keys": 0, "projection": 1, "reconstruction": 2, "debug_xi": 3}
+PHILOX_LAYOUTS = {"scalar_keys": 0, "projection": 1, "reconstruction": 2, "debug_xi": 3, "projection_sub_tiles": 4}
 
 
 def core_debug_philox_layout(layout: str | int, seed: int, rnd: int, j0: int, nj: int, q0: int, nq: int,

@@ -57,13 +57,13 @@ struct Plan {
                            // m in kPlanSmall)
     uint32_t narrow_tiles; // tiles of 64 vectors after those, given to project_narrow_kernel (whole waves of
                            // vectors that would not fill a block of 256)
-    uint32_t tail_begin;   // first vector given to the lanes-over-coordinates kernel (= m when it gets none)
-    uint32_t tail_groups;  // its groups of qj vectors: all vectors in kPlanCoords; in kPlanVectors the
-                           // last m mod 64 when they are too few for a wave of their own; else 0
+    uint32_t sub_tiles;    // tiles of sub_jw vectors after those, same kernel with the lanes of a wave split
+    uint32_t sub_jw;       // between vectors and Philox blocks (8, 16 or 32; 0 when there are none)
+    uint32_t tail_groups;  // kPlanCoords: groups of qj vectors of the lanes-over-coordinates kernel; else 0
     uint32_t qj;           // vectors per block of that kernel (4 or 8)
     uint32_t nchunks;
-    uint32_t tiles_per_chunk;   // in 256-coordinate tiles; a multiple of 4 whenever tail_groups > 0, because
-                                // the lanes-over-coordinates kernel walks 1024-coordinate tiles
+    uint32_t tiles_per_chunk;   // in 256-coordinate tiles; a multiple of 4 in kPlanCoords, whose kernel walks
+                                // 1024-coordinate tiles
     uint32_t Z;            // slices of the cross-chunk sum
     uint32_t small_threads;   // kPlanSmall: threads per workgroup
     bool wide;             // more than 32 clients: passes of up to 64 on the matrix pipe
@@ -76,13 +76,16 @@ struct Plan {
 // gradient (8 clients, projection alone), 64 vectors as a quarter-filled block 1.71 ms, 320 vectors as
 // one full and one quarter-filled tile 6.34 ms against 3.35 ms for 256.  So: a rest above 192 fills all
 // four waves of one more block of 256; otherwise its whole waves go to blocks of 64 vectors whose four
-// waves share the chunk's coordinates (project_narrow_kernel), and a last part of at most 48 vectors
-// goes to the lanes-over-coordinates kernel, where every lane works whatever the count is -- unless the
-// chunks, which all launches of a plan share, are shorter than 32 tiles: that kernel needs long chunks,
-// and then (or above 48 vectors) the last part gets a block of 64 of its own.
+// waves share the chunk's coordinates (project_narrow_kernel), and what is left after those to blocks
+// of 8, 16 or 32 vectors of the same kernel (lanes split between vectors and Philox blocks), in the
+// size that pads the count least (the larger one on a tie); more than 48 left-over vectors take a full
+// block of 64 instead.  Measured there with 8 clients, projection + sums: 8 / 16 / 32 / 48 vectors
+// 0.17 / 0.29 / 0.53 / 0.77 ms, and at 2^23 coordinates 0.075 / 0.11 / 0.18 / 0.26 ms (the
+// lanes-over-coordinates kernel: 0.18 / 0.30 / 0.58 / 0.83 and 0.12 / 0.14 / 0.21 / 0.31 ms).
 constexpr uint32_t kRestFullTile = 192;
-constexpr uint32_t kTailMax = 48;
-constexpr uint64_t kTailMinTilesPerChunk = 32;
+constexpr uint32_t kSubTilesMaxVectors = 48;
+// Fewer vectors than this on a gradient that is not tiny: the lanes-over-coordinates kernel.
+constexpr uint32_t kVectorsPlanMin = 5;
 
 constexpr uint64_t kSmallMaxD = 65536;      // kPlanSmall: a thread's fp32 chain stays <= 256 terms
 constexpr uint32_t kSmallMaxClients = 8;
@@ -135,9 +138,10 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
     p.small_threads = 0;
     p.qj = 0;
     p.wide = false;
-    p.tail_begin = m;
     p.tail_groups = 0;
     p.narrow_tiles = 0;
+    p.sub_tiles = 0;
+    p.sub_jw = 0;
     if (!force_vectors && small_ok && (forced == kVariantSmall || (forced == kVariantAuto && little_work))) {
         // one Philox block per thread where d allows it: the serial chain of a thread is what a
         // launch-bound round waits for
@@ -151,56 +155,37 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
     } else {
         // which vectors go to which kernel
         bool coords_all = false;
-        uint32_t main_tiles = (uint32_t)ceil_div(m, kThreads), narrow = 0, qvectors = 0;
-        // chunk length for about 8192 blocks in the launch of the 256-vector tiles, or in the launch of
-        // the 64-vector tiles when there is no other
-        // More than 32 clients: wide passes for the 256-vector tiles, with chunks of at most 16 tiles, if
-        // those shorter chunks still give a launchable grid.
-        auto chunk_tiles = [&](uint32_t mt, uint32_t nw, bool& wide) {
-            uint64_t want = ceil_div(kTargetBlocks, mt ? mt : (nw ? nw : 1u));
-            if (want < 1) want = 1;
-            if (want > tiles_total) want = tiles_total;
-            uint64_t tpc = ceil_div(tiles_total, want);
-            if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
-            wide = false;
-            if (mt > 0 && n > kMaxClientsPerPassMfma && forced != kVariantValu) {
-                const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
-                const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
-                if (ceil_div(chunks_wide, 8) * 8 * mt <= kMaxGridBlocks) {
-                    wide = true;
-                    tpc = tpc_wide;
-                }
-            }
-            return tpc;
-        };
-        bool wide = false;
+        uint32_t main_tiles = (uint32_t)ceil_div(m, kThreads), narrow = 0, sub_tiles = 0, sub_jw = 0;
         if (!force_vectors) {
             if (forced == kVariantQ || forced == kVariantSmall) coords_all = true;
-            else coords_all = little_work || m <= kTailMax;
+            else coords_all = little_work || m < kVectorsPlanMin;
             if (!coords_all && rem > 0 && rem <= kRestFullTile) {
                 main_tiles = full_tiles;
                 narrow = rem / 64;
-                qvectors = rem % 64;
-                if (qvectors > kTailMax || (qvectors > 0 && chunk_tiles(main_tiles, narrow, wide) < kTailMinTilesPerChunk)) {
-                    narrow += 1;
-                    qvectors = 0;
+                const uint32_t left = rem % 64;
+                if (left > 0) {
+                    // more than 48 vectors: a full tile of 64 is faster than 7 or 8 small ones
+                    uint32_t best_jw = 64, best_pad = 64;
+                    for (uint32_t jw = 32; jw >= 8 && left <= kSubTilesMaxVectors; jw /= 2) {
+                        const uint32_t padded = (uint32_t)ceil_div(left, jw) * jw;
+                        if (padded < best_pad) { best_pad = padded; best_jw = jw; }
+                    }
+                    if (best_jw == 64) narrow += 1;
+                    else { sub_jw = best_jw; sub_tiles = best_pad / best_jw; }
                 }
             }
         }
-        if (coords_all) qvectors = m;
         const uint64_t qtiles = ceil_div(d, (uint64_t)kThreads * 4);
-        if (qvectors) {
-            // 8 vectors per block share every load of G when there is enough work to fill the chip
-            // with such blocks; 4 otherwise (more, shorter blocks)
-            p.qj = (qvectors > 4 && ceil_div(qvectors, 8) * qtiles >= 2 * kBlockSlots) ? 8 : 4;
-            p.tail_begin = m - qvectors;
-            p.tail_groups = (uint32_t)ceil_div(qvectors, p.qj);
-        }
-        const bool tail = !coords_all && qvectors > 0;
         p.narrow_tiles = narrow;
+        p.sub_tiles = sub_tiles;
+        p.sub_jw = sub_jw;
         if (coords_all) {
             p.mode = kPlanCoords;
             p.jtiles = 0;
+            // 8 vectors per block share every load of G when there is enough work to fill the chip
+            // with such blocks; 4 otherwise (more, shorter blocks)
+            p.qj = (m > 4 && ceil_div(m, 8) * qtiles >= 2 * kBlockSlots) ? 8 : 4;
+            p.tail_groups = (uint32_t)ceil_div(m, p.qj);
             uint64_t want = ceil_div(kTargetBlocks / 2, p.tail_groups);
             if (want < 1) want = 1;
             if (want > qtiles) want = qtiles;
@@ -211,12 +196,33 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
         } else {
             p.mode = kPlanVectors;
             p.jtiles = main_tiles;
-            uint64_t tpc = chunk_tiles(main_tiles, narrow, wide);
-            p.wide = wide;
-            if (tail) tpc = ceil_div(tpc, 4) * 4;   // the lanes-over-coordinates kernel walks whole 1024-coordinate tiles
-            // both side kernels add one fp32 sum per step of at most 1024 coordinates into the chunk
-            // sum: keep that chain no longer than the main kernel's
-            if ((tail || narrow) && tpc > 4 * kQTilesPerChunkMax) tpc = 4 * kQTilesPerChunkMax;
+            // chunk length for about 8192 blocks in the launch of the 256-vector tiles, or in a
+            // launch of smaller tiles when there is no other
+            // (the one with the fewest tiles: the others then launch more blocks, which does no harm)
+            const uint32_t side = narrow > sub_tiles ? narrow : sub_tiles;
+            const uint32_t fewest = (narrow && sub_tiles) ? (narrow < sub_tiles ? narrow : sub_tiles) : side;
+            uint64_t want = ceil_div(kTargetBlocks, main_tiles ? main_tiles : (fewest ? fewest : 1u));
+            if (want < 1) want = 1;
+            if (want > tiles_total) want = tiles_total;
+            uint64_t tpc = ceil_div(tiles_total, want);
+            if (tpc > kTilesPerChunkMax) tpc = kTilesPerChunkMax;
+            // more than 32 clients: wide passes for the 256-vector tiles, with chunks of at most 16 tiles,
+            // if those shorter chunks still give a launchable grid
+            if (main_tiles > 0 && n > kMaxClientsPerPassMfma && forced != kVariantValu) {
+                const uint64_t tpc_wide = tpc < kTilesPerChunkWide ? tpc : kTilesPerChunkWide;
+                const uint64_t chunks_wide = ceil_div(tiles_total, tpc_wide);
+                if (ceil_div(chunks_wide, 8) * 8 * main_tiles <= kMaxGridBlocks) {
+                    p.wide = true;
+                    tpc = tpc_wide;
+                }
+            }
+            // a wave of the smaller tiles adds one fp32 sum per step of 64 coordinates into its chunk sum
+            // and takes every fourth step, i.e. one sum per 256-coordinate tile: chunks of at most 256
+            // tiles there, the chain length those kernels were checked with
+            if (side > 0 && tpc > kTilesPerChunkMax / 4) tpc = kTilesPerChunkMax / 4;
+            // the waves of a block of 8, 16 or 32 vectors take whole tiles in turn: chunks of a multiple
+            // of 4 tiles keep them level
+            if (sub_tiles > 0) tpc = ceil_div(tpc, 4) * 4;
             p.tiles_per_chunk = (uint32_t)tpc;
             p.nchunks = (uint32_t)ceil_div(tiles_total, tpc);
         }
@@ -225,6 +231,7 @@ bool make_plan(uint64_t d, uint32_t m, uint32_t n, bool allow_qmode, int forced,
     const uint64_t chunk_slots = ceil_div(p.nchunks, 8) * 8;
     uint64_t widest = p.jtiles > p.tail_groups ? p.jtiles : p.tail_groups;
     if (p.narrow_tiles > widest) widest = p.narrow_tiles;
+    if (p.sub_tiles > widest) widest = p.sub_tiles;
     const uint64_t grid = p.mode == kPlanSmall ? (uint64_t)p.jtiles : chunk_slots * widest;
     if (grid > kMaxGridBlocks) return false;
     uint32_t Z = p.nchunks / 128u;
@@ -315,6 +322,24 @@ hipError_t launch_project_narrow(const ProjectArgs& a, bool bf16, uint32_t block
                 : launch(project_narrow_kernel<NC, false>, g, b, st, a);
 }
 
+template <int NC, int JW>
+hipError_t launch_project_sub_jw(const ProjectArgs& a, bool bf16, uint32_t blocks, hipStream_t st)
+{
+    const dim3 g(blocks), b(kThreads);
+    return bf16 ? launch(project_sub_kernel<NC, true, JW>, g, b, st, a)
+                : launch(project_sub_kernel<NC, false, JW>, g, b, st, a);
+}
+
+template <int NC>
+hipError_t launch_project_sub(const ProjectArgs& a, bool bf16, uint32_t jw, uint32_t blocks, hipStream_t st)
+{
+    switch (jw) {
+        case 8:  return launch_project_sub_jw<NC, 8>(a, bf16, blocks, st);
+        case 16: return launch_project_sub_jw<NC, 16>(a, bf16, blocks, st);
+        default: return launch_project_sub_jw<NC, 32>(a, bf16, blocks, st);
+    }
+}
+
 template <int NC>
 hipError_t launch_project(const ProjectArgs& a, bool bf16, bool store_xi, uint32_t blocks, hipStream_t st)
 {
@@ -381,6 +406,37 @@ int validate_reconstruct(uint64_t d, uint32_t m, const float* pbar, const float*
     if (!pbar || !gtilde) return CORE_ERR_INVALID_ARGUMENT;
     if (d == 0 || d > kMaxD || m == 0 || m > kMaxM) return CORE_ERR_INVALID_ARGUMENT;
     if (!aligned_to(pbar, 4) || !aligned_to(gtilde, 4)) return CORE_ERR_MISALIGNED;
+    return CORE_OK;
+}
+
+// Tiles of jw vectors starting at vector j_begin: jw = 64 in passes of at most 16 clients
+// (project_narrow_kernel), jw = 8, 16 or 32 in passes of at most 8 (project_sub_kernel).
+int enqueue_narrow(const ProjectArgs& a, bool bf16, uint32_t n, uint32_t jw, uint32_t tiles, uint32_t j_begin,
+                   uint32_t chunk_slots, hipStream_t st)
+{
+    ProjectArgs w = a;
+    w.jtiles = tiles;
+    w.j_begin = j_begin;
+    const uint32_t blocks = chunk_slots * tiles;
+    const uint32_t cap = jw == 64 ? kMaxClientsPerPass : 8u;
+    for (uint32_t c0 = 0; c0 < n; c0 += cap) {
+        const uint32_t nc = (n - c0 < cap) ? (n - c0) : cap;
+        w.c0 = c0; w.nc = nc;
+        hipError_t e;
+        if (jw == 64) {
+            if (nc <= 1)      e = launch_project_narrow<1>(w, bf16, blocks, st);
+            else if (nc <= 2) e = launch_project_narrow<2>(w, bf16, blocks, st);
+            else if (nc <= 4) e = launch_project_narrow<4>(w, bf16, blocks, st);
+            else if (nc <= 8) e = launch_project_narrow<8>(w, bf16, blocks, st);
+            else              e = launch_project_narrow<16>(w, bf16, blocks, st);
+        } else {
+            if (nc <= 1)      e = launch_project_sub<1>(w, bf16, jw, blocks, st);
+            else if (nc <= 2) e = launch_project_sub<2>(w, bf16, jw, blocks, st);
+            else if (nc <= 4) e = launch_project_sub<4>(w, bf16, jw, blocks, st);
+            else              e = launch_project_sub<8>(w, bf16, jw, blocks, st);
+        }
+        if (e != hipSuccess) return hip_fail(e);
+    }
     return CORE_OK;
 }
 
@@ -466,27 +522,20 @@ int enqueue_compress(uint64_t seed, uint64_t round, uint64_t d, uint32_t m, uint
             if (e != hipSuccess) return hip_fail(e);
         }
     }
-    if (plan.narrow_tiles > 0) {   // 64-vector blocks of the lanes-over-vectors kernel: whole waves of the rest
-        ProjectArgs w = a;
-        w.jtiles = plan.narrow_tiles;
-        w.j_begin = plan.jtiles * (uint32_t)kThreads;
-        const uint32_t blocks = chunk_slots * plan.narrow_tiles;
-        for (uint32_t c0 = 0; c0 < n; c0 += kMaxClientsPerPass) {
-            const uint32_t nc = (n - c0 < kMaxClientsPerPass) ? (n - c0) : kMaxClientsPerPass;
-            w.c0 = c0; w.nc = nc;
-            hipError_t e;
-            if (nc <= 1)      e = launch_project_narrow<1>(w, bf16, blocks, st);
-            else if (nc <= 2) e = launch_project_narrow<2>(w, bf16, blocks, st);
-            else if (nc <= 4) e = launch_project_narrow<4>(w, bf16, blocks, st);
-            else if (nc <= 8) e = launch_project_narrow<8>(w, bf16, blocks, st);
-            else              e = launch_project_narrow<16>(w, bf16, blocks, st);
-            if (e != hipSuccess) return hip_fail(e);
-        }
+    uint32_t j_next = plan.jtiles * (uint32_t)kThreads;
+    if (plan.narrow_tiles > 0) {   // whole waves of the rest: blocks of 64 vectors
+        const int rc = enqueue_narrow(a, bf16, n, 64, plan.narrow_tiles, j_next, chunk_slots, st);
+        if (rc != CORE_OK) return rc;
+        j_next += plan.narrow_tiles * 64u;
     }
-    if (plan.tail_groups > 0) {   // lanes-over-coordinates kernel: all vectors, or the last m mod 64
+    if (plan.sub_tiles > 0) {      // what is left: blocks of 8, 16 or 32 vectors
+        const int rc = enqueue_narrow(a, bf16, n, plan.sub_jw, plan.sub_tiles, j_next, chunk_slots, st);
+        if (rc != CORE_OK) return rc;
+    }
+    if (plan.tail_groups > 0) {   // lanes-over-coordinates kernel (kPlanCoords): all vectors
         ProjectArgs q = a;
         q.jtiles = plan.tail_groups;
-        q.j_begin = plan.tail_begin;
+        q.j_begin = 0;
         q.tiles_per_chunk = plan.tiles_per_chunk / 4;   // its tiles are 1024 coordinates
         const uint32_t blocks = chunk_slots * plan.tail_groups;
         for (uint32_t c0 = 0; c0 < n; c0 += 8) {
@@ -1033,17 +1082,17 @@ int core_debug_plan(uint64_t d, uint32_t m, uint32_t n, uint64_t plan[10])
     plan[3] = p.mode == kPlanCoords ? p.tiles_per_chunk / 4 : p.tiles_per_chunk;
     plan[4] = p.Z;
     plan[5] = p.mode == kPlanSmall ? (uint64_t)p.jtiles : chunk_slots * plan[1];
-    plan[6] = p.mode == kPlanVectors ? (uint64_t)(m - p.tail_begin) : 0;
+    plan[6] = p.sub_tiles;
     plan[7] = p.qj;
     plan[8] = p.narrow_tiles;
-    plan[9] = 0;
+    plan[9] = p.sub_jw;
     return CORE_OK;
 }
 
 int core_debug_philox_layout(int layout, uint64_t seed, uint64_t round, uint32_t j0, uint32_t nj, uint64_t q0,
                              uint64_t nq, uint32_t* out, core_stream stream)
 {
-    if (!out || layout < 0 || layout > 3 || nj == 0 || nq == 0) return CORE_ERR_INVALID_ARGUMENT;
+    if (!out || layout < 0 || layout > 4 || nj == 0 || nq == 0) return CORE_ERR_INVALID_ARGUMENT;
     if ((uint64_t)j0 + nj > (1ull << 32) || nq > (1ull << 32) || q0 + nq > (1ull << 32) ||
         (uint64_t)nj * nq > (1ull << 28))
         return CORE_ERR_INVALID_ARGUMENT;
@@ -1054,13 +1103,14 @@ int core_debug_philox_layout(int layout, uint64_t seed, uint64_t round, uint32_t
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
     a.r0 = (uint32_t)round; a.r1 = (uint32_t)(round >> 32);
     a.j0 = j0; a.nj = nj; a.q0 = q0; a.nq = nq; a.out = out;
-    const uint64_t threads = layout == 1 ? nj : nq;
+    const uint64_t threads = layout == 1 ? nj : layout == 4 ? (uint64_t)nj * nq : nq;
     const dim3 g((uint32_t)ceil_div(threads, kThreads)), b(kThreads);
     hipError_t e;
     switch (layout) {
         case 1: e = launch(debug_philox_kernel<1>, g, b, (hipStream_t)stream, a); break;
         case 2: e = launch(debug_philox_kernel<2>, g, b, (hipStream_t)stream, a); break;
         case 3: e = launch(debug_philox_kernel<3>, g, b, (hipStream_t)stream, a); break;
+        case 4: e = launch(debug_philox_kernel<4>, g, b, (hipStream_t)stream, a); break;
         default: e = launch(debug_philox_kernel<0>, g, b, (hipStream_t)stream, a); break;
     }
     return e == hipSuccess ? CORE_OK : hip_fail(e);

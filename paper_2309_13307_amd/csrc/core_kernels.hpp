@@ -536,6 +536,124 @@ template <> struct RawG4<true> {
     }
 };
 
+// The lanes-over-vectors projection for tiles of JW = 8, 16 or 32 vectors: what is left of m mod 256
+// after its whole waves, and few vectors on a long gradient.  As in project_narrow_kernel the four
+// waves of a block take the same JW vectors and share the chunk's coordinates, wave w taking the
+// 256-coordinate tiles w, w + 4, ... of the chunk and staging each in its own part of LDS; but the
+// lanes of a wave split further: lane l works on vector a.j_begin + JW jt + (l mod JW) and, of the 64
+// Philox blocks of a tile, on those congruent to l / JW modulo 64 / JW, so every lane is busy whatever
+// the vector count.  The 64 / JW partial sums of a vector are added across the lanes once per chunk
+// (butterfly over the upper lane bits), then the four waves' sums in wave order, and the block writes
+// one partial sum per (vector, client) like a block of project_kernel.  a.jtiles counts tiles of JW
+// vectors.  With so few generator calls per coordinate the loads of G must be wide and early: a lane
+// fetches 4 consecutive coordinates per client with one 64- or 128-bit load where the rows allow it,
+// a whole tile ahead, and keeps them in their stored form until the tile is used (with 64-coordinate
+// steps and element loads the kernel took 0.37 ms at the ResNet-50 size whatever JW was, waiting for
+// memory).  No block barrier in the loop: a wave's part of LDS is written and read by that wave
+// alone, and the LDS operations of one wave are performed in program order.
+template <int NC, bool BF16, int JW>
+__global__ void __launch_bounds__(kThreads) project_sub_kernel(ProjectArgs a)
+{
+    static_assert(JW == 32 || JW == 16 || JW == 8, "vectors per tile");
+    static_assert(NC <= 8, "LDS: four waves x NC x 256 floats");
+    constexpr int QW = 64 / JW;             // lane groups of a wave, each with its own Philox blocks
+    constexpr int kCalls = (kTile / 4) / QW;   // generator calls per lane per tile
+    __shared__ __attribute__((aligned(16))) float tile[kThreads / 64][NC][kTile];
+    __shared__ float red[kThreads / 64][NC][JW];
+
+    const uint32_t b = blockIdx.x;
+    const uint32_t xcd = b & 7u;
+    const uint32_t s = b >> 3;
+    const uint32_t chunk = (s / a.jtiles) * 8u + xcd;
+    const uint32_t jt = s % a.jtiles;
+    if (chunk >= a.nchunks) return;
+
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    const uint32_t w = (uint32_t)__builtin_amdgcn_readfirstlane((int)(t >> 6));   // wave-uniform, so scalar
+    const uint32_t jl = lane % JW, qs = lane / JW;
+    const uint32_t j = a.j_begin + jt * JW + jl;
+
+    const uint64_t tiles_total = (a.d + kTile - 1) / kTile;
+    const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk;
+    uint64_t tile_end = tile_begin + a.tiles_per_chunk;
+    if (tile_end > tiles_total) tile_end = tiles_total;
+
+    // lanes differ in q and in j: every round after the first is fully divergent
+    Generator<1, 1> gen;
+    gen.init(a.k0, a.k1, a.round_dev ? a.round_dev[0] : a.r0, a.round_dev ? a.round_dev[1] : a.r1);
+
+    float acc_outer[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc_outer[c] = 0.0f;
+
+    // register prefetch of this wave's next tile: lane l holds coordinates 256 tile + 4 l .. + 3 of every client
+    RawG4<BF16> pre[NC];
+    const bool vec = a.vec_load != 0;
+    auto fetch = [&](uint64_t tl) {
+        const uint64_t i = tl * kTile + 4 * lane;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (tl < tile_end && (uint32_t)c < a.nc) pre[c].load(a.G, (uint64_t)(a.c0 + c) * a.ld + i, i, a.d, vec);
+            else pre[c].zero();
+        }
+    };
+    fetch(tile_begin + w);
+
+    for (uint64_t tl = tile_begin + w; tl < tile_end; tl += 4) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            float g[4];
+            pre[c].widen(g);
+            *reinterpret_cast<float4*>(&tile[w][c][4 * lane]) = make_float4(g[0], g[1], g[2], g[3]);
+        }
+        __builtin_amdgcn_wave_barrier();
+        fetch(tl + 4);
+
+        float acc[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
+        const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
+#pragma unroll 2
+        for (int k = 0; k < kCalls; ++k) {
+            const uint32_t qq = qs + (uint32_t)(QW * k);
+            float z0, z1, z2, z3;
+            gen.block(q0 + qq, j, z0, z1, z2, z3);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 g = *reinterpret_cast<const float4*>(&tile[w][c][4 * qq]);
+                acc[c] = fmaf(z0, g.x, acc[c]);
+                acc[c] = fmaf(z1, g.y, acc[c]);
+                acc[c] = fmaf(z2, g.z, acc[c]);
+                acc[c] = fmaf(z3, g.w, acc[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc_outer[c] += acc[c];
+    }
+
+    // the lane groups of a vector: butterfly over the lane bits above log2(JW)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int off = JW; off < 64; off <<= 1) acc_outer[c] += __shfl_xor(acc_outer[c], off, 64);
+    }
+    if (qs == 0) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) red[w][c][jl] = acc_outer[c];
+    }
+    __syncthreads();
+    if (w == 0 && qs == 0 && j < a.m) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if ((uint32_t)c < a.nc) {
+                const float tot = ((red[0][c][jl] + red[1][c][jl]) + red[2][c][jl]) + red[3][c][jl];
+                a.part[((uint64_t)chunk * a.n + a.c0 + c) * a.m + j] = kXiScale * tot;
+            }
+        }
+    }
+}
+
 template <int NC, bool BF16, int QJ>
 __global__ void __launch_bounds__(kThreads) project_q_kernel(ProjectArgs a)
 {
@@ -1246,6 +1364,13 @@ __global__ void __launch_bounds__(kThreads) debug_philox_kernel(DebugPhiloxArgs 
             const Words w = gen.words(q, a.j0 + jj);
             if (t < a.nq) put(jj, t, w);
         }
+    } else if constexpr (LAYOUT == 4) {
+        // lanes over vectors and Philox blocks at once (tiles of fewer than 64 vectors)
+        Generator<1, 1> gen;
+        gen.init(a.k0, a.k1, a.r0, a.r1);
+        const uint64_t jj = t % a.nj, qq = t / a.nj;
+        const Words w = gen.words((uint32_t)(a.q0 + qq), a.j0 + (uint32_t)jj);
+        if (qq < a.nq) put(jj, qq, w);
     } else {
         Generator<(LAYOUT == 3 ? 4 : 10), (LAYOUT == 3 ? 4 : 10)> gen;
         gen.init(a.k0, a.k1, a.r0, a.r1);

@@ -146,7 +146,7 @@ def test_debug_exports_arguments():
     L = core.load_library()
     E = binding
     f = L.core_debug_philox_layout
-    assert f(4, 1, 0, 0, 1, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
+    assert f(5, 1, 0, 0, 1, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
     assert f(-1, 1, 0, 0, 1, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
     assert f(1, 1, 0, 0, 0, 0, 1, FAKE, None) == E.ERR_INVALID_ARGUMENT
     assert f(1, 1, 0, 0, 1, 0, 0, FAKE, None) == E.ERR_INVALID_ARGUMENT
@@ -385,28 +385,32 @@ def test_launch_plan_invariants():
             assert p["tiles_per_chunk"] <= 16 and threads <= 1024   # fp32 chain of a thread: <= 64 terms
             return
         tiles_c = p["tiles_per_chunk"]
+        narrow, sub, jw = p["narrow_tiles"], p["sub_tiles"], p["sub_tile_vectors"]
         if p["mode"] == 1:
-            assert p["vectors_per_block"] in (4, 8) and p["tail_vectors"] == 0 and p["narrow_tiles"] == 0
+            assert p["vectors_per_block"] in (4, 8) and narrow == 0 and sub == 0 and jw == 0
             assert tiles_c <= 64
             tiles = -(-d // 1024)
             assert (p["jtiles"] - 1) * p["vectors_per_block"] < m <= p["jtiles"] * p["vectors_per_block"]
         else:
-            assert tiles_c <= 1024
+            assert tiles_c <= 1024 and p["vectors_per_block"] == 0
             tiles = -(-d // 256)
-            # the rest m mod 256 may go to tiles of 64 vectors and, its last few vectors, to a
-            # lanes-over-coordinates launch; together the three launches cover every vector once
-            tail, narrow = p["tail_vectors"], p["narrow_tiles"]
-            if tail == 0 and narrow == 0:
-                assert (p["jtiles"] - 1) * 256 < m <= p["jtiles"] * 256
+            # the rest m mod 256 may go to tiles of 64 vectors and what is left of it to tiles of 8, 16 or
+            # 32; together the launches cover every vector once, padding the last tile only
+            if narrow == 0 and sub == 0:
+                assert (p["jtiles"] - 1) * 256 < m <= p["jtiles"] * 256 and jw == 0
             else:
                 rest = m - 256 * p["jtiles"]
-                assert 0 < rest <= 192 and rest == m % 256 and 0 <= tail <= 48 and narrow <= 3
-                assert 64 * (narrow - 1) < rest - tail <= 64 * narrow
-                assert tiles_c <= 256
-                if tail:
-                    assert p["vectors_per_block"] in (4, 8) and tiles_c % 4 == 0 and tiles_c >= 32
+                assert 0 < rest <= 192 and rest == m % 256 and narrow <= 3 and tiles_c <= 256
+                left = rest - 64 * narrow
+                if sub:
+                    assert jw in (8, 16, 32) and 0 < left <= 48 and (sub - 1) * jw < left <= sub * jw
+                    assert sub * jw < 64 and tiles_c % 4 == 0
+                    # no other tile size pads less
+                    assert all(-(-left // w) * w >= sub * jw for w in (8, 16, 32))
+                else:
+                    assert jw == 0 and -64 < left <= 0
                 chunk_slots = -(-p["nchunks"] // 8) * 8
-                assert chunk_slots * max(narrow, -(-tail // 4)) < (1 << 31)
+                assert chunk_slots * max(narrow, sub) < (1 << 31)
         assert (p["nchunks"] - 1) * tiles_c < tiles <= p["nchunks"] * tiles_c
         assert p["nchunks"] * p["jtiles"] <= p["blocks"] < (1 << 31)
         assert 1 <= p["slices"] <= 16
@@ -416,29 +420,30 @@ def test_launch_plan_invariants():
     # the headline shapes keep the plan the profiles were taken with
     assert core.core_debug_plan(25_557_032, 1024, 8) == {
         "mode": 0, "jtiles": 4, "nchunks": 2038, "tiles_per_chunk": 49, "slices": 15, "blocks": 8160,
-        "tail_vectors": 0, "vectors_per_block": 0, "narrow_tiles": 0}
+        "sub_tiles": 0, "vectors_per_block": 0, "narrow_tiles": 0, "sub_tile_vectors": 0}
     p5 = core.core_debug_plan(124_439_808, 4096, 16)
     assert (p5["mode"], p5["jtiles"], p5["tiles_per_chunk"]) == (0, 16, 950)
     # the two launch-bound shapes take the one-launch plan, one Philox block per thread
     assert core.core_debug_plan(1024, 16, 4) == {
         "mode": 2, "jtiles": 16, "nchunks": 1, "tiles_per_chunk": 1, "slices": 1, "blocks": 16,
-        "tail_vectors": 0, "vectors_per_block": 0, "narrow_tiles": 0}
+        "sub_tiles": 0, "vectors_per_block": 0, "narrow_tiles": 0, "sub_tile_vectors": 0}
     assert core.core_debug_plan(4096, 64, 8)["mode"] == 2
     assert core.core_debug_plan(4096, 64, 9)["mode"] == 1          # more than 8 clients
-    assert core.core_debug_plan(1 << 20, 16, 4)["mode"] == 1       # few vectors, long gradient
-    # up to 48 vectors on a long gradient: lanes over coordinates, 8 vectors per block
-    p48 = core.core_debug_plan(25_557_032, 48, 8)
-    assert (p48["mode"], p48["jtiles"], p48["vectors_per_block"]) == (1, 6, 8)
-    # vector counts that do not fill tiles of 256: whole waves to blocks of 64 vectors; a short rest to the
-    # lanes-over-coordinates kernel where the chunks are long enough for it, else one more block of 64;
-    # more than 192 to one more tile of 256
+    assert core.core_debug_plan(1 << 17, 16, 4)["mode"] == 1       # little work: lanes over coordinates
+    p4 = core.core_debug_plan(25_557_032, 4, 8)                     # fewer than 5 vectors as well
+    assert (p4["mode"], p4["jtiles"], p4["vectors_per_block"]) == (1, 1, 4)
+    # vector counts that do not fill tiles of 256: whole waves to tiles of 64 vectors, what is left to tiles
+    # of 8, 16 or 32 (the size that pads least), more than 48 left over to one more tile of 64, more than
+    # 192 in all to one more tile of 256
     def split(m):
         p = core.core_debug_plan(25_557_032, m, 8)
-        return (p["mode"], p["jtiles"], p["narrow_tiles"], p["tail_vectors"])
-    assert split(49) == (0, 0, 1, 0) and split(64) == (0, 0, 1, 0) and split(100) == (0, 0, 2, 0)
-    assert split(128) == (0, 0, 2, 0) and split(192) == (0, 0, 3, 0) and split(193) == (0, 1, 0, 0)
-    assert split(320) == (0, 1, 1, 0) and split(300) == (0, 1, 1, 0) and split(1000) == (0, 4, 0, 0)
-    assert split(1088) == (0, 4, 1, 0) and split(1100) == (0, 4, 1, 12) and split(1024 + 190) == (0, 4, 3, 0)
+        return (p["mode"], p["jtiles"], p["narrow_tiles"], p["sub_tiles"], p["sub_tile_vectors"])
+    assert split(5) == (0, 0, 0, 1, 8) and split(16) == (0, 0, 0, 1, 16) and split(20) == (0, 0, 0, 3, 8)
+    assert split(32) == (0, 0, 0, 1, 32) and split(48) == (0, 0, 0, 3, 16) and split(49) == (0, 0, 1, 0, 0)
+    assert split(64) == (0, 0, 1, 0, 0) and split(100) == (0, 0, 1, 5, 8) and split(128) == (0, 0, 2, 0, 0)
+    assert split(192) == (0, 0, 3, 0, 0) and split(193) == (0, 1, 0, 0, 0) and split(300) == (0, 1, 0, 3, 16)
+    assert split(320) == (0, 1, 1, 0, 0) and split(1000) == (0, 4, 0, 0, 0) and split(1088) == (0, 4, 1, 0, 0)
+    assert split(1100) == (0, 4, 1, 1, 16) and split(1108) == (0, 4, 1, 3, 8) and split(1024 + 190) == (0, 4, 3, 0, 0)
     # sizes whose grid would not be launchable are refused up front
     import ctypes
     out = (ctypes.c_uint64 * 10)()

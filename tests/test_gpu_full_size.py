@@ -120,13 +120,12 @@ def test_resnet50_size_with_50_clients_sampled():
 @pytest.mark.timeout(300)
 def test_resnet50_size_with_a_vector_count_split_over_three_launches():
     """m = 1108 at the ResNet-50 size: four tiles of 256 vectors, one tile of 64 and the last 20 vectors
-    by the lanes-over-coordinates kernel (which only long chunks admit, so small shapes never take
-    that path); 4 clients.  Sampled vectors from each of the three parts over the full d, and sampled
-    coordinate blocks over all m."""
+    as three tiles of 8 (lanes split between vectors and Philox blocks); 4 clients.  Sampled vectors
+    from each of the three parts over the full d, and sampled coordinate blocks over all m."""
     case = workloads.config4(DEV, m=1108, n=4)
     plan = core.core_debug_plan(case.d, case.m, case.n)
     _say(f"config4 shape with m={case.m} n={case.n}: plan {plan}")
-    assert (plan["mode"], plan["jtiles"], plan["narrow_tiles"], plan["tail_vectors"]) == (0, 4, 1, 20)
+    assert (plan["mode"], plan["jtiles"], plan["narrow_tiles"], plan["sub_tiles"], plan["sub_tile_vectors"]) == (0, 4, 1, 3, 8)
     ws = core.alloc_workspace(case.d, case.m, case.n)
     P, pbar = core.core_compress_batched(case.seed, 1, case.G, case.m, ws=ws)
     pbar2, gtilde = core.core_round(case.seed, 1, case.G, case.m, ws=ws)

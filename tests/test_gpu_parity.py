@@ -63,7 +63,7 @@ PHILOX_WINDOWS = [
 ]
 
 
-@pytest.mark.parametrize("layout", ["scalar_keys", "projection", "reconstruction", "debug_xi"])
+@pytest.mark.parametrize("layout", ["scalar_keys", "projection", "reconstruction", "debug_xi", "projection_sub_tiles"])
 @pytest.mark.parametrize("seed,rnd,j0,nj,q0,nq", PHILOX_WINDOWS)
 def test_philox_words_bit_exact_in_every_kernel_layout(layout, seed, rnd, j0, nj, q0, nq):
     """Algorithm 1, REQUIRE line: all machines share one generator, so the uint32 stream must be
@@ -460,26 +460,30 @@ def test_streams_and_graph_capture():
 
 @pytest.mark.parametrize("d,m,n,bf16", [
     (60000, 320, 8, False),     # one tile of 256 vectors + one tile of 64
-    (40000, 600, 3, True),      # 512 + 64 + 24 in a tile of 64 of their own (short chunks)
-    (53000, 257, 16, True),     # 256 on the matrix pipe + 1, the rest in two passes of 8 clients
-    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 64 + 12, the tiles of 64 in passes of 16 clients
-    (300000, 130, 2, False),    # two tiles of 64 + 2 in a third
+    (40000, 600, 3, True),      # 512 + 64 + 24 as three tiles of 8
+    (53000, 257, 16, True),     # 256 on the matrix pipe + 1 (a tile of 8), the tile in two passes of 8 clients
+    (24000, 1100, 40, True),    # wide pass (chunks of 16 tiles) + 64 + 12 (a tile of 16), 40 clients in passes
+    (300000, 130, 2, False),    # two tiles of 64 + 2 (a tile of 8)
     (66000, 200, 4, False),     # 200 vectors: one block of 256, all four waves busy
     (70001, 513, 2, False),     # 512 + 1
-    (270000, 49, 5, True),      # one tile of 64, 49 of 64 lanes
-    (270000, 48, 5, True),      # lanes over coordinates throughout
+    (270000, 49, 5, True),      # seven tiles of 8
+    (270000, 48, 5, True),      # three tiles of 16
+    (270001, 32, 8, True),      # one tile of 32, rows not a multiple of 4: element loads
+    (270000, 17, 3, False),     # three tiles of 8, the last with one vector
+    (1300000, 5, 1, False),     # one tile of 8 with 5 vectors
     (90000, 190, 20, False),    # three tiles of 64 (the last with 62 lanes), 20 clients in passes of 16
-    (40000, 447, 7, True),      # 256 + 3 x 64 (191 = 2 x 64 + 63: the 63 get a tile of their own)
+    (40000, 447, 7, True),      # 256 + 2 x 64 + 63 (a full tile of 64: nothing pads less)
+    (200000, 100, 9, True),     # 64 + 36 as five tiles of 8, 9 clients: passes of 8 + 1 in the small tiles
 ])
 def test_ragged_vector_counts_split_between_the_projections(d, m, n, bf16):
     """Vector counts that are not multiples of 256, on shapes with enough work for the
     lanes-over-vectors plan: the library's own choice gives whole tiles of 256 to blocks of four
-    waves, whole waves of the rest to blocks of 64 vectors whose waves share the chunk, and a short
-    remainder to one more such block (the lanes-over-coordinates kernel takes it only where chunks are
-    long: that path is covered at full size); all launches write the same per-chunk partial sums."""
+    waves, whole waves of the rest to blocks of 64 vectors whose waves share the chunk, and what is left
+    to blocks of 8, 16 or 32 vectors whose lanes split between vectors and Philox blocks; all launches
+    write the same per-chunk partial sums."""
     plan = core.core_debug_plan(d, m, n)
     _say(f"ragged vector count d={d} m={m} n={n} bf16={bf16} plan={plan}")
-    assert plan["mode"] in (0, 1)
+    assert plan["mode"] == 0
     rng = np.random.default_rng(d + 3 * m + n)
     G = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(DEV)
     if bf16:
