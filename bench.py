@@ -48,10 +48,10 @@ OPS_GENERATE = 26
 # compiled kernels at those shapes: they are reported only while the kernel sources still hash to
 # `kernel_id`, and as null otherwise.
 COUNTERS = {
-    "kernel_id": "55bb963166ad31bb",
+    "kernel_id": "978a2c596fb6e32e",
     "config4": {
         "source": "profiles/core_round_config4.md", "date": "2026-11-27",
-        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200632 * 2 * 1024, "write_bytes": 65216 * 1024},
+        "project": {"SQ_INSTS_VALU": 9.13251e9, "fetch_bytes": 200631 * 2 * 1024, "write_bytes": 65216 * 1024},
         "reconstruct": {"SQ_INSTS_VALU": 6.10726e9, "fetch_bytes": 41 * 2 * 1024, "write_bytes": 99832.2 * 1024},
     },
     "config5": {

@@ -40,15 +40,14 @@ struct ProjectArgs {
     uint32_t k0, k1;      // seed halves
     uint32_t r0, r1;      // round halves
     const uint32_t* round_dev;   // when non-null, the round counter (lo, hi) is read from here instead
-    uint32_t jtiles;      // vector tiles of this launch: tiles of kThreads vectors, or groups of QJ vectors
-    uint32_t j_begin;     // lanes-over-coordinates kernel: first vector of this launch (its groups cover
-                          // j_begin .. m-1; the vectors below belong to a lanes-over-vectors launch)
+    uint32_t jtiles;      // vector tiles of this launch: tiles of 256, 64 or JW vectors, or groups of QJ vectors
+    uint32_t j_begin;     // first vector of this launch (the small-tile launches follow the tiles of 256)
     uint32_t nchunks;     // chunks of d
     uint32_t tiles_per_chunk;
     float* part;          // [nchunks][n][m]
     float* xi_store;      // materialised variant only: [ceil(d/4)][m][4], else unused
-    int vec_load;         // lanes-over-coordinates kernel: rows of G start on 16-byte (fp32) / 8-byte (bf16)
-                          // boundaries, so a thread may fetch its 4 coordinates with one load
+    int vec_load;         // rows of G start on 16-byte (fp32) / 8-byte (bf16) boundaries, so a thread of the
+                          // kernels that fetch 4 coordinates per lane may do it with one load
 };
 
 template <bool BF16>
@@ -467,10 +466,10 @@ project_mfma_wide_kernel(ProjectArgs a)
     }
 }
 
-// Projection for few vectors, for the last m mod 256 vectors of a larger problem, or for little work.
-// With lanes over the vectors a block of 256 threads needs 256 vectors to keep its four waves busy (and
-// the busy waves of partly filled blocks pile up on the same SIMDs); here lanes run over the Philox
-// block q, as in the reconstruction, so every lane works whatever the number of vectors is.  A block owns QJ consecutive vectors and a
+// Projection for very few vectors or for little work.  With lanes over the vectors a block of 256
+// threads needs 256 vectors to keep its four waves busy (and the busy waves of partly filled blocks
+// pile up on the same SIMDs); here lanes run over the Philox block q, as in the reconstruction, so
+// every lane works whatever the number of vectors is.  A block owns QJ consecutive vectors and a
 // chunk of 1024-coordinate tiles; each thread loads G for its 4 coordinates once per tile (one 64- or
 // 128-bit load per client when the rows allow it) and keeps it in registers for all QJ vectors, so
 // there is no LDS traffic in the loop; the QJ x NC sums are combined across the block once per chunk
