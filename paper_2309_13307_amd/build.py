@@ -16,7 +16,8 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libcore_hip.so")
 
 SOURCES = ["core_api.hip"]
-HEADERS = ["core_rng.hpp", "core_kernels.hpp"]
+HEADERS = ["core_rng.hpp", "core_common.hpp", "core_kernels.hpp", "core_project.hpp", "core_project_few.hpp",
+           "core_reduce.hpp", "core_reconstruct.hpp", "core_steps.hpp", "core_debug.hpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
