@@ -80,7 +80,7 @@ struct Plan {
 // of 8, 16 or 32 vectors of the same kernel (lanes split between vectors and Philox blocks), in the
 // size that pads the count least (the larger one on a tie); more than 48 left-over vectors take a full
 // block of 64 instead.  Measured there with 8 clients, projection + sums: 8 / 16 / 32 / 48 vectors
-// 0.17 / 0.29 / 0.53 / 0.77 ms, and at 2^23 coordinates 0.075 / 0.11 / 0.18 / 0.26 ms (the
+// 0.17 / 0.28 / 0.52 / 0.75 ms, and at 2^23 coordinates 0.070 / 0.10 / 0.17 / 0.25 ms (the
 // lanes-over-coordinates kernel: 0.18 / 0.30 / 0.58 / 0.83 and 0.12 / 0.14 / 0.21 / 0.31 ms).
 constexpr uint32_t kRestFullTile = 192;
 constexpr uint32_t kSubTilesMaxVectors = 48;

@@ -179,29 +179,72 @@ template <> struct RawG4<true> {
     }
 };
 
+// The same for 2 consecutive coordinates (one 32- or 64-bit load).
+template <bool BF16> struct RawG2;
+
+template <> struct RawG2<false> {
+    float v[2];
+    __device__ __forceinline__ void load(const void* G, uint64_t base, uint64_t i, uint64_t d, bool vec)
+    {
+        if (vec && i + 2 <= d) {
+            const float2 x = *reinterpret_cast<const float2*>((const float*)G + base);
+            v[0] = x.x; v[1] = x.y;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) v[k] = (i + k < d) ? ((const float*)G)[base + k] : 0.0f;
+        }
+    }
+    __device__ __forceinline__ void zero() { v[0] = v[1] = 0.0f; }
+    __device__ __forceinline__ void widen(float (&g)[2]) const { g[0] = v[0]; g[1] = v[1]; }
+};
+
+template <> struct RawG2<true> {
+    uint32_t lo;   // a bf16 pair
+    __device__ __forceinline__ void load(const void* G, uint64_t base, uint64_t i, uint64_t d, bool vec)
+    {
+        const uint16_t* p = (const uint16_t*)G + base;
+        if (vec && i + 2 <= d) {
+            lo = *reinterpret_cast<const uint32_t*>(p);
+        } else {
+            const uint32_t e0 = (i < d) ? (uint32_t)p[0] : 0u, e1 = (i + 1 < d) ? (uint32_t)p[1] : 0u;
+            lo = e0 | (e1 << 16);
+        }
+    }
+    __device__ __forceinline__ void zero() { lo = 0u; }
+    __device__ __forceinline__ void widen(float (&g)[2]) const
+    {
+        g[0] = __uint_as_float(lo << 16); g[1] = __uint_as_float(lo & 0xffff0000u);
+    }
+};
+
 // The lanes-over-vectors projection for tiles of JW = 8, 16 or 32 vectors: what is left of m mod 256
 // after its whole waves, and few vectors on a long gradient.  As in project_narrow_kernel the four
 // waves of a block take the same JW vectors and share the chunk's coordinates, wave w taking the
-// 256-coordinate tiles w, w + 4, ... of the chunk and staging each in its own part of LDS; but the
-// lanes of a wave split further: lane l works on vector a.j_begin + JW jt + (l mod JW) and, of the 64
-// Philox blocks of a tile, on those congruent to l / JW modulo 64 / JW, so every lane is busy whatever
+// 128-coordinate trips w, w + 4, ... of the chunk and staging each in its own part of LDS; but the
+// lanes of a wave split further: lane l works on vector a.j_begin + JW jt + (l mod JW) and, of the 32
+// Philox blocks of a trip, on those congruent to l / JW modulo 64 / JW, so every lane is busy whatever
 // the vector count.  The 64 / JW partial sums of a vector are added across the lanes once per chunk
 // (butterfly over the upper lane bits), then the four waves' sums in wave order, and the block writes
 // one partial sum per (vector, client) like a block of project_kernel.  a.jtiles counts tiles of JW
 // vectors.  With so few generator calls per coordinate the loads of G must be wide and early: a lane
-// fetches 4 consecutive coordinates per client with one 64- or 128-bit load where the rows allow it,
-// a whole tile ahead, and keeps them in their stored form until the tile is used (with 64-coordinate
+// fetches 2 consecutive coordinates per client with one 32- or 64-bit load where the rows allow it,
+// a whole trip ahead, and keeps them in their stored form until the trip is used (with 64-coordinate
 // steps and element loads the kernel took 0.37 ms at the ResNet-50 size whatever JW was, waiting for
-// memory).  No block barrier in the loop: a wave's part of LDS is written and read by that wave
-// alone, and the LDS operations of one wave are performed in program order.
+// memory).  Trips of 128 rather than 256 coordinates keep a block at 16 KB of LDS for 8 clients, so
+// that registers and not LDS bound the waves per SIMD: 3 to 10 % faster.  No block barrier in the
+// loop: a wave's part of LDS is written and read by that wave alone, and the LDS operations of one
+// wave are performed in program order.
+constexpr int kSubTrip = 128;   // coordinates a wave stages at a time (32 Philox blocks)
+
 template <int NC, bool BF16, int JW>
 __global__ void __launch_bounds__(kThreads) project_sub_kernel(ProjectArgs a)
 {
     static_assert(JW == 32 || JW == 16 || JW == 8, "vectors per tile");
-    static_assert(NC <= 8, "LDS: four waves x NC x 256 floats");
+    static_assert(NC <= 8, "LDS: four waves x NC x 128 floats");
+    constexpr int TRIP = kSubTrip;
     constexpr int QW = 64 / JW;             // lane groups of a wave, each with its own Philox blocks
-    constexpr int kCalls = (kTile / 4) / QW;   // generator calls per lane per tile
-    __shared__ __attribute__((aligned(16))) float tile[kThreads / 64][NC][kTile];
+    constexpr int kCalls = (TRIP / 4) / QW;   // generator calls per lane per trip
+    __shared__ __attribute__((aligned(16))) float tile[kThreads / 64][NC][TRIP];
     __shared__ float red[kThreads / 64][NC][JW];
 
     const uint32_t b = blockIdx.x;
@@ -216,9 +259,10 @@ __global__ void __launch_bounds__(kThreads) project_sub_kernel(ProjectArgs a)
     const uint32_t jl = lane % JW, qs = lane / JW;
     const uint32_t j = a.j_begin + jt * JW + jl;
 
-    const uint64_t tiles_total = (a.d + kTile - 1) / kTile;
-    const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk;
-    uint64_t tile_end = tile_begin + a.tiles_per_chunk;
+    // trips of TRIP coordinates; a.tiles_per_chunk counts tiles of 256
+    const uint64_t tiles_total = (a.d + TRIP - 1) / TRIP;
+    const uint64_t tile_begin = (uint64_t)chunk * a.tiles_per_chunk * (kTile / TRIP);
+    uint64_t tile_end = tile_begin + (uint64_t)a.tiles_per_chunk * (kTile / TRIP);
     if (tile_end > tiles_total) tile_end = tiles_total;
 
     // lanes differ in q and in j: every round after the first is fully divergent
@@ -229,11 +273,11 @@ __global__ void __launch_bounds__(kThreads) project_sub_kernel(ProjectArgs a)
 #pragma unroll
     for (int c = 0; c < NC; ++c) acc_outer[c] = 0.0f;
 
-    // register prefetch of this wave's next tile: lane l holds coordinates 256 tile + 4 l .. + 3 of every client
-    RawG4<BF16> pre[NC];
+    // register prefetch of this wave's next trip: lane l holds coordinates 128 trip + 2 l, + 1 of every client
+    RawG2<BF16> pre[NC];
     const bool vec = a.vec_load != 0;
     auto fetch = [&](uint64_t tl) {
-        const uint64_t i = tl * kTile + 4 * lane;
+        const uint64_t i = tl * TRIP + 2 * lane;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             if (tl < tile_end && (uint32_t)c < a.nc) pre[c].load(a.G, (uint64_t)(a.c0 + c) * a.ld + i, i, a.d, vec);
@@ -246,9 +290,9 @@ __global__ void __launch_bounds__(kThreads) project_sub_kernel(ProjectArgs a)
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            float g[4];
+            float g[2];
             pre[c].widen(g);
-            *reinterpret_cast<float4*>(&tile[w][c][4 * lane]) = make_float4(g[0], g[1], g[2], g[3]);
+            *reinterpret_cast<float2*>(&tile[w][c][2 * lane]) = make_float2(g[0], g[1]);
         }
         __builtin_amdgcn_wave_barrier();
         fetch(tl + 4);
@@ -256,7 +300,7 @@ __global__ void __launch_bounds__(kThreads) project_sub_kernel(ProjectArgs a)
         float acc[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
-        const uint32_t q0 = (uint32_t)(tl * (kTile / 4));
+        const uint32_t q0 = (uint32_t)(tl * (TRIP / 4));
 #pragma unroll 2
         for (int k = 0; k < kCalls; ++k) {
             const uint32_t qq = qs + (uint32_t)(QW * k);
