@@ -414,6 +414,37 @@ def test_random_shapes(d, m, n, bf16, pad, variant):
     _run_and_check(1000 + d, m * n, G, m, d=d, what=f"random d={d} m={m} n={n}")
 
 
+def _random_long_shapes(count, seed):
+    """Shapes with enough work for the lanes-over-vectors plans (tiles of 256, 64 and 8 / 16 / 32 vectors
+    in every combination), small enough for the oracle: d m (n + 1) <= 2e8."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        d = int(rng.integers(60_000, 400_000))
+        m = int(rng.choice([rng.integers(5, 64), rng.integers(64, 256), rng.integers(256, 700)]))
+        n = int(rng.choice([1, 2, 3, 5, 8, 9, 17]))
+        if -(-m // 64) * -(-d // 256) <= 1024 or d * m * (n + 1) > 2e8:
+            continue
+        out.append((d, m, n, bool(rng.integers(0, 2)), int(rng.integers(0, 6))))
+    return out
+
+
+@pytest.mark.parametrize("d,m,n,bf16,pad", _random_long_shapes(14, 77))
+def test_random_long_shapes(d, m, n, bf16, pad):
+    """Seeded random shapes on gradients long enough for the library to choose the lanes-over-vectors
+    plans by itself, with whatever mix of tile sizes the vector count asks for; padded rows make some of
+    them take the element-load paths."""
+    plan = core.core_debug_plan(d, m, n)
+    _say(f"random long shape d={d} m={m} n={n} bf16={bf16} pad={pad} plan={plan}")
+    assert plan["mode"] == 0
+    rng = np.random.default_rng(d * 131 + m * 17 + n)
+    full = torch.from_numpy((rng.standard_normal((n, d + pad)) * rng.uniform(1e-3, 10.0)).astype(np.float32)).to(DEV)
+    if bf16:
+        full = full.to(torch.bfloat16)
+    G = full[:, :d] if pad else full
+    _run_and_check(2000 + d, m + n, G, m, d=d, what=f"random long d={d} m={m} n={n}")
+
+
 def test_streams_and_graph_capture():
     """Entry points only enqueue on the given stream: they work on side streams, two streams with
     their own scratch can run at once, and a captured HIP graph replays to the eager result."""
